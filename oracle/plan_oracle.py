@@ -1,0 +1,84 @@
+"""Plain reference of the ragged work partition.  TEST INFRASTRUCTURE ONLY.
+
+The decode attention step over a batch of requests with two cache kinds
+(Section 4.2: the cache type is chosen per request; Section 4.3: one cache map
+per request) is cut into independent work items, one per (request, head, token
+range).  The paper does not prescribe an intra-kernel partition; the rule below
+is this build's, stated in full so that the library's planner can be checked
+against it bit for bit:
+
+* a request of n tokens is cut into ceil(n / C) ranges [s*C, min(n, (s+1)*C)),
+  with C = hidden_chunk for hidden-kind and C = kv_chunk for KV-kind requests;
+* split_count[r] = number of ranges of request r; ws_offset[r] = sum of
+  split_count over requests before r (request order);
+* the partial result of (request r, range s, head h) is stored in slot
+  (ws_offset[r] + s) * H + h;
+* items are listed hidden-kind first, then KV-kind; within a kind by request,
+  then range, then head; an item is (r, h, t0, t1).
+
+Block arithmetic of the cache map (Section 4.3): token j of a request lives in
+its (j // block_size)-th block at slot j % block_size; a request of n tokens owns
+ceil(n / block_size) blocks per cached vector type (K and V for the KV kind, the
+input hidden vector for the hidden kind).
+"""
+KIND_KV = 0
+KIND_HIDDEN = 1
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk):
+    B = len(ctx_lens)
+    split_count, ws_offset = [], []
+    run = 0
+    for r in range(B):
+        n = int(ctx_lens[r])
+        if n < 1:
+            raise ValueError("ctx_len must be >= 1")
+        if int(cache_kind[r]) not in (KIND_KV, KIND_HIDDEN):
+            raise ValueError("unknown cache kind")
+        c = hidden_chunk if int(cache_kind[r]) == KIND_HIDDEN else kv_chunk
+        split_count.append(ceil_div(n, c))
+        ws_offset.append(run)
+        run += split_count[-1]
+    items = []
+    n_hidden_items = 0
+    for kind in (KIND_HIDDEN, KIND_KV):
+        c = hidden_chunk if kind == KIND_HIDDEN else kv_chunk
+        for r in range(B):
+            if int(cache_kind[r]) != kind:
+                continue
+            n = int(ctx_lens[r])
+            for s in range(split_count[r]):
+                for h in range(n_heads):
+                    items.append((r, h, s * c, min(n, (s + 1) * c)))
+        if kind == KIND_HIDDEN:
+            n_hidden_items = len(items)
+    return {
+        "split_count": split_count,
+        "ws_offset": ws_offset,
+        "items": items,
+        "n_hidden_items": n_hidden_items,
+        "n_partials": run,
+    }
+
+
+def partial_slot(ws_offset, n_heads, r, s, h):
+    return (ws_offset[r] + s) * n_heads + h
+
+
+def token_location(block_list, block_size, j):
+    """(block id, slot) of token j given the request's list of blocks."""
+    return block_list[j // block_size], j % block_size
+
+
+def blocks_for(n_tokens, block_size):
+    return ceil_div(n_tokens, block_size)
+
+
+def cache_bytes(n_tokens, d_model, elem_bytes, kind):
+    """Bytes of cached vectors for n tokens of one layer (un-padded)."""
+    per_token = d_model * elem_bytes
+    return n_tokens * per_token * (1 if kind == KIND_HIDDEN else 2)

@@ -1,0 +1,204 @@
+/*
+ * apt_hybrid.h - C ABI of the MI355X (gfx950) hybrid-cache decode attention library.
+ *
+ * One decode step of one Transformer layer's attention over a ragged batch in
+ * which every request keeps its context either in a paged KV cache or in a
+ * hidden cache: the layer's input hidden vectors, from which K and V are
+ * projected again on the fly (Section 3.1, "Opportunity I: Utilizing Hybrid
+ * Cache"; Section 2.1, Eq. 1-3 for the attention itself; Section 2.2 for the KV
+ * cache and block-wise storage; Section 4.3 for the unified block pool and the
+ * per-request cache map).
+ *
+ * For request r (n = ctx_lens[r] attended positions, the current token
+ * included and already present in the cache) and head h:
+ *     KV kind:      k_j, v_j read from the request's K and V blocks
+ *     hidden kind:  k_j = x_j W_K[:, h] + b_K[h],  v_j = x_j W_V[:, h] + b_V[h]    (Eq. 1)
+ *     out[r][h] = sum_j softmax_j(softmax_scale * <q[r][h], k_j>) v_j              (Eq. 2-3)
+ * The output projection W_o of Eq. 3 is NOT applied.
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary.  Every function returns 0
+ *     (APT_OK) or a negative apt_status; apt_strerror() names it.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *     memory of the current device.  The caller owns every buffer.  The library
+ *     allocates no device memory and keeps no state between calls.
+ *   - Launching functions take a HIP stream as void* (NULL = default stream) and
+ *     return after enqueueing; inputs are read-only, only `out`, `workspace`,
+ *     and `packed` (apt_pack_weights) are written.
+ *   - Arguments are validated on the host before anything is launched.  Block
+ *     ids inside block_tables are NOT range-checked on the device; use
+ *     apt_validate_host() on a host copy.
+ *
+ * Memory layout (T = element type of apt_shape.dtype)
+ *   pool block       block_size * d_model elements of T.  The three pool base
+ *                    pointers may alias one unified pool: a block holds K, V or
+ *                    hidden vectors of block_size consecutive token positions
+ *                    (Section 4.3).
+ *   hidden block     T [slot][d_model]
+ *   K block, V block T [head][slot][head_dim]
+ *   block_tables     int32 [B][2][max_blocks_per_req] (device): row 0 = K blocks
+ *                    (KV kind) or hidden blocks (hidden kind), row 1 = V blocks
+ *                    (KV kind).  Token j is in entry j / block_size at slot
+ *                    j % block_size.  Entries past the request's last block and
+ *                    the unused slots of the last block are never read.
+ *   q                T [B][n_heads][head_dim]
+ *   W_K, W_V         T [d_in = d_model][d_out = n_heads*head_dim] row-major, so
+ *                    that k = x W + b; this is the transpose of an [out][in]
+ *                    linear-layer weight (the paper writes W x for column vectors).
+ *   b_K, b_V         T [d_model]
+ *   out              [B][n_heads][head_dim] of apt_shape.out_dtype
+ */
+#ifndef APT_HYBRID_H
+#define APT_HYBRID_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum apt_status {
+    APT_OK = 0,
+    APT_EINVAL = -1,     /* null pointer, non-positive count, bad length or kind */
+    APT_ESHAPE = -2,     /* unsupported or inconsistent shape                     */
+    APT_EDTYPE = -3,     /* unknown dtype / unsupported out_dtype                 */
+    APT_EWORKSPACE = -4, /* workspace or plan buffer too small                    */
+    APT_EHIP = -5,       /* a HIP runtime call failed                             */
+    APT_ERANGE = -6      /* a block id or length is out of range                  */
+} apt_status;
+
+enum { APT_F32 = 0, APT_F16 = 1, APT_BF16 = 2 };
+enum { APT_KIND_KV = 0, APT_KIND_HIDDEN = 1 };
+enum { APT_HIDDEN_AUTO = 0, APT_HIDDEN_VALU = 1, APT_HIDDEN_MFMA = 2 };
+
+typedef struct apt_shape {
+    int32_t d_model;            /* = n_heads * head_dim                                   */
+    int32_t n_heads;
+    int32_t head_dim;           /* 64 or 128                                               */
+    int32_t block_size;         /* tokens per cache block; 16 (or 4, 8, 32)               */
+    int32_t dtype;              /* APT_F32 / APT_F16 / APT_BF16: q, pools, W, b           */
+    int32_t out_dtype;          /* APT_F32 or the same as dtype                           */
+    int32_t max_blocks_per_req; /* row length of block_tables                             */
+    int32_t hidden_chunk;       /* tokens per hidden-kind work item; 0 = library default  */
+    int32_t kv_chunk;           /* tokens per KV-kind work item; 0 = library default      */
+    int32_t hidden_impl;        /* APT_HIDDEN_AUTO: MFMA kernel for 16-bit dtypes with
+                                   head_dim 128, plain-ALU kernel otherwise               */
+    float softmax_scale;        /* multiplies <q, k>; 1/sqrt(head_dim) in Eq. 2's
+                                   multi-head reading                                     */
+    int32_t reserved;           /* must be 0                                              */
+} apt_shape;
+
+typedef struct apt_plan_info {
+    int32_t batch;
+    int32_t n_items;            /* work items = workgroups of the attention launch        */
+    int32_t n_hidden_items;     /* the first n_hidden_items items are hidden-kind         */
+    int32_t n_partials;         /* sum over requests of their token ranges                */
+    int32_t hidden_chunk;       /* resolved values                                        */
+    int32_t kv_chunk;
+    int32_t hidden_impl;        /* resolved: APT_HIDDEN_VALU or APT_HIDDEN_MFMA           */
+    int32_t reserved;
+    int64_t total_tokens;
+    int64_t hidden_tokens;
+    uint64_t plan_bytes;        /* bytes of the plan blob actually used                   */
+    uint64_t workspace_bytes;   /* device workspace apt_hybrid_decode_attn needs          */
+} apt_plan_info;
+
+const char* apt_strerror(int status);
+
+/* Library version (major*10000 + minor*100 + patch). */
+int apt_version(void);
+
+/*
+ * Size in bytes of the largest plan blob a batch of B requests with contexts of at
+ * most max_ctx tokens can need (host and device copy have the same size).
+ */
+int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
+
+/*
+ * Ragged work partitioner (host).  Cuts the batch into work items
+ * (request, head, token range) of the two cache kinds, hidden-kind items first,
+ * so that one launch serves both (the cache type is a per-request decision,
+ * Section 4.2; requests of both types share a batch, Section 4.3).
+ *   ctx_lens_host   int32 [B], every entry >= 1 and <= max_blocks_per_req*block_size
+ *   cache_kind_host uint8 [B], APT_KIND_KV or APT_KIND_HIDDEN
+ *   plan_host       caller's buffer of plan_bytes bytes (see apt_plan_max_bytes); filled
+ *                   with a self-contained blob of int32 words:
+ *                     [0..15] header, [16..16+B) split_count, then ws_offset[B],
+ *                     then (padded to a multiple of 4 words) items[n_items][4] =
+ *                     (request, head, t0, t1)
+ *   info            optional, receives the counts and the workspace size
+ * The rule: a request of n tokens is cut into ceil(n/C) ranges [s*C, min(n,(s+1)*C)),
+ * C = hidden_chunk or kv_chunk by kind; ws_offset is the exclusive prefix sum of
+ * split_count in request order; the partial result of (r, range s, head h) lives in
+ * slot (ws_offset[r]+s)*n_heads + h; items are ordered hidden kind first, then by
+ * request, range, head.  Integer-only; the same inputs always give the same bytes.
+ * Errors: APT_EINVAL (null, B < 1, length < 1, unknown kind), APT_ERANGE (length
+ * beyond max_blocks_per_req*block_size), APT_EWORKSPACE (plan_bytes too small),
+ * APT_ESHAPE / APT_EDTYPE (bad shape).
+ */
+int apt_plan(const apt_shape* s, const int32_t* ctx_lens_host, const uint8_t* cache_kind_host, int B,
+             void* plan_host, size_t plan_bytes, apt_plan_info* info);
+
+/* Read the counts back from a plan blob made by apt_plan (host). */
+int apt_plan_get_info(const void* plan_host, apt_plan_info* info);
+
+/* Asynchronous copy of a plan blob to device memory (plan_dev: at least
+ * info.plan_bytes bytes).  plan_host must stay unchanged until the copy is done;
+ * use page-locked host memory for a truly asynchronous copy. */
+int apt_plan_upload(const void* plan_host, void* plan_dev, void* stream);
+
+/*
+ * Debug helper (host): range-check a host copy of the cache maps.  Every entry of
+ * the first ceil(n/block_size) positions of the rows a request uses must lie in
+ * [0, n_pool_blocks).  Returns APT_ERANGE on the first violation.
+ */
+int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens_host, const uint8_t* cache_kind_host,
+                      const int32_t* block_tables_host, int B, int64_t n_pool_blocks);
+
+/*
+ * One-off re-layout of a layer's projection weights for the MFMA kernel (Eq. 1's
+ * W_k, W_v restricted to one head at a time).  Needed only when the resolved
+ * hidden_impl is APT_HIDDEN_MFMA.  `packed` (device) needs apt_packed_weight_bytes()
+ * bytes = 2 * d_model^2 elements.  Layout of `packed`, in 16-byte units of 8 elements:
+ *   [head][k-tile of 64 inputs][row 0..255][unit 0..7], row < 128: W_K output channel
+ *   head*128+row, row >= 128: W_V output channel head*128+row-128; the unit holding
+ *   inputs k-tile*64 + 8*c .. +7 sits at position c ^ ((row ^ (row >> 3)) & 7).
+ */
+int apt_packed_weight_bytes(const apt_shape* s, size_t* bytes);
+int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void* packed, void* stream);
+
+/*
+ * The decode attention step for one layer (Eq. 1-3 over both cache kinds).
+ *   plan_host / plan_dev   the blob from apt_plan and its device copy
+ *   q, k_pages, v_pages, hidden_pages, b_K, b_V, block_tables, out   device, see layout
+ *   W_K, W_V    device, raw [d_in][d_out]; read only by the plain-ALU hidden kernel
+ *               (may be NULL when the resolved hidden_impl is MFMA or no request is
+ *               hidden-kind)
+ *   W_packed    device, from apt_pack_weights; read only by the MFMA hidden kernel
+ *               (may be NULL otherwise)
+ *   workspace   device, at least info.workspace_bytes bytes; holds the per-range
+ *               partial results (running maximum, sum, un-normalised output) that the
+ *               merge kernel combines; contents are undefined afterwards
+ * Two kernels are enqueued on `stream`: the item kernel (one workgroup per work item,
+ * hidden-kind and KV-kind items in the same launch) and the merge kernel.
+ * Errors: APT_EINVAL (null pointer that is needed), APT_EWORKSPACE, APT_ESHAPE,
+ * APT_EDTYPE, APT_EHIP (launch failure; nothing is written in the other cases).
+ */
+int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
+                           const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                           const void* W_K, const void* W_V, const void* W_packed,
+                           const void* b_K, const void* b_V, const int32_t* block_tables,
+                           void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16; device
+ * pointers, 16-byte aligned).  Exists so that hardware traffic counters can be
+ * calibrated against a kernel of known traffic (reads `bytes`, writes `bytes`).
+ */
+int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APT_HYBRID_H */

@@ -1,0 +1,732 @@
+// HIP kernels (gfx950) of the hybrid-cache decode attention step and their launchers.
+//
+//   items kernel   one workgroup (4 wavefronts of 64) per work item of the plan:
+//                    KV-kind item      streams the K and V rows of one head over a token
+//                                      range, online softmax per 16-lane group (HBM bound)
+//                    hidden-kind item  projects K_h, V_h of a 256-token tile from the
+//                                      gathered hidden rows on MFMA (or on plain ALUs
+//                                      for fp32) and attends to them from registers
+//                  every item writes one partial (m, l, acc[head_dim]) in fp32
+//   merge kernel   combines a request's partials per head and normalises
+//
+// Scores are kept in base-2 units: s2 = softmax_scale*log2(e)*<q,k>, weights 2^(s2 - m).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "apt_internal.h"
+
+namespace {
+
+constexpr float kSentinel = -1.0e30f;   // "no score yet": finite, so differences never give NaN
+constexpr int kThreads = 256;
+
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+struct ItemParams {
+    const int32_t* plan;          // device blob
+    const char* q;
+    const char* k_pages;
+    const char* v_pages;
+    const char* hidden_pages;
+    const char* W_K;
+    const char* W_V;
+    const char* W_packed;
+    const char* b_K;
+    const char* b_V;
+    const int32_t* block_tables;
+    float* ws_acc;                // [n_slots][HD]
+    float2* ws_ml;                // [n_slots]
+    int32_t B, H, d, bs, log2_bs, max_blocks;
+    int32_t n_items, n_hidden_items, hidden_chunk, kv_chunk, items_off;
+    float scale_log2e;
+};
+
+// ---------------------------------------------------------------------------------
+// element helpers.  DT: 0 = fp32, 1 = fp16, 2 = bf16
+// ---------------------------------------------------------------------------------
+template <int DT> struct Elt { static constexpr int bytes = DT == 0 ? 4 : 2; static constexpr int per16 = 16 / bytes; };
+
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+template <int DT> __device__ inline float load_elem(const char* base, int64_t idx) {
+    if constexpr (DT == 0) return ((const float*)base)[idx];
+    else if constexpr (DT == 1) return (float)((const _Float16*)base)[idx];
+    else return bf16_to_f32(((const uint16_t*)base)[idx]);
+}
+
+// 16 bytes -> Elt<DT>::per16 floats
+template <int DT> __device__ inline void cvt16(const uint4& v, float* out) {
+    if constexpr (DT == 0) {
+        out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y);
+        out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
+    } else if constexpr (DT == 1) {
+        h8_t h = __builtin_bit_cast(h8_t, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (float)h[i];
+    } else {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+}
+
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------------------------
+// cross-lane helpers
+// ---------------------------------------------------------------------------------
+template <int CTRL> __device__ inline float dpp_mov(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+// Sum over the aligned group of LANES lanes a lane belongs to; every lane gets the sum.
+template <int LANES> __device__ inline float group_sum(float x) {
+    x += dpp_mov<0xB1>(x);                          // quad_perm [1,0,3,2]
+    x += dpp_mov<0x4E>(x);                          // quad_perm [2,3,0,1]
+    if constexpr (LANES >= 8) x += dpp_mov<0x141>(x);   // row_half_mirror
+    if constexpr (LANES >= 16) x += dpp_mov<0x140>(x);  // row_mirror
+    if constexpr (LANES >= 32) x += __shfl_xor(x, 16);
+    if constexpr (LANES >= 64) x += __shfl_xor(x, 32);
+    return x;
+}
+template <int LANES> __device__ inline float group_max(float x) {
+    x = fmaxf(x, dpp_mov<0xB1>(x));
+    x = fmaxf(x, dpp_mov<0x4E>(x));
+    if constexpr (LANES >= 8) x = fmaxf(x, dpp_mov<0x141>(x));
+    if constexpr (LANES >= 16) x = fmaxf(x, dpp_mov<0x140>(x));
+    if constexpr (LANES >= 32) x = fmaxf(x, __shfl_xor(x, 16));
+    if constexpr (LANES >= 64) x = fmaxf(x, __shfl_xor(x, 32));
+    return x;
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---------------------------------------------------------------------------------
+// KV-kind item
+// ---------------------------------------------------------------------------------
+// K/V block layout [head][slot][HD]: the rows of one (block, head) are one contiguous run
+// of bs*HD elements, read as 1 KB wave loads (64 lanes x 16 B).  LPR lanes share a row,
+// 64/LPR rows per load.  A lane group keeps its own online-softmax state for the rows it
+// sees; the groups are combined through LDS at the end.
+constexpr int kKvUnits = 4;   // 1 KB loads of K (and of V) per pipeline stage
+
+template <int DT, int HD>
+__device__ void kv_item(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+    constexpr int EB = Elt<DT>::bytes;
+    constexpr int EPL = Elt<DT>::per16;          // elements per lane per load
+    constexpr int LPR = HD * EB / 16;            // lanes per row
+    constexpr int RPL = 64 / LPR;                // rows per 1 KB load
+    constexpr int G = 4 * RPL;                   // lane groups in the workgroup
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int bs = p.bs;
+    const int log2_nl = p.log2_bs - __builtin_ctz(RPL);     // loads per page per matrix = bs/RPL
+    const int nl_mask = (1 << log2_nl) - 1;
+    const int64_t blk_bytes = (int64_t)bs * p.d * EB;
+    const int64_t head_off = (int64_t)h * bs * HD * EB;
+
+    const int p0 = t0 >> p.log2_bs;
+    const int p1 = (t1 + bs - 1) >> p.log2_bs;
+    // pages of this wave: p0 + w, p0 + w + 4, ...
+    const int npg = (p1 - p0 - w + 3) >> 2;
+    const int nunits = npg > 0 ? (npg << log2_nl) : 0;
+
+    // lane i holds the block ids of the wave's i-th page
+    int32_t kid = 0, vid = 0;
+    if (lane < npg) {
+        const int64_t e = (int64_t)r * 2 * p.max_blocks + p0 + w + 4 * lane;
+        kid = p.block_tables[e];
+        vid = p.block_tables[e + p.max_blocks];
+    }
+
+    // q for the lane's channels, pre-scaled
+    const int c0 = (lane % LPR) * EPL;
+    float qf[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+        qf[i] = load_elem<DT>(p.q, ((int64_t)r * p.H + h) * HD + c0 + i) * p.scale_log2e;
+
+    float m = kSentinel, l = 0.f, acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+
+    uint4 kb[2][kKvUnits], vb[2][kKvUnits];
+    auto issue = [&](int g, uint4* kbuf, uint4* vbuf) {
+#pragma unroll
+        for (int i = 0; i < kKvUnits; ++i) {
+            const int u = g * kKvUnits + i;
+            if (u < nunits) {
+                const int pg = u >> log2_nl;
+                const int64_t kblk = __builtin_amdgcn_readlane(kid, pg);
+                const int64_t vblk = __builtin_amdgcn_readlane(vid, pg);
+                const int64_t off = head_off + (int64_t)(u & nl_mask) * 1024 + lane * 16;
+                kbuf[i] = *(const uint4*)(p.k_pages + kblk * blk_bytes + off);
+                vbuf[i] = *(const uint4*)(p.v_pages + vblk * blk_bytes + off);
+            }
+        }
+    };
+    auto consume = [&](int g, const uint4* kbuf, const uint4* vbuf) {
+        float s[kKvUnits];
+        bool ok[kKvUnits];
+        float mn = m;
+#pragma unroll
+        for (int i = 0; i < kKvUnits; ++i) {
+            const int u = g * kKvUnits + i;
+            const int pg = u >> log2_nl;
+            const int tok = ((p0 + w + 4 * pg) << p.log2_bs) + (u & nl_mask) * RPL + lane / LPR;
+            ok[i] = (u < nunits) && (tok < t1);
+            float kf[EPL];
+            cvt16<DT>(kbuf[i], kf);
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) part = fmaf(kf[e], qf[e], part);
+            part = group_sum<LPR>(part);
+            s[i] = ok[i] ? part : kSentinel;
+            mn = fmaxf(mn, s[i]);
+        }
+        const float alpha = fast_exp2(m - mn);
+        l *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int i = 0; i < kKvUnits; ++i) {
+            const float pw = ok[i] ? fast_exp2(s[i] - mn) : 0.f;
+            l += pw;
+            float vf[EPL];
+            cvt16<DT>(vbuf[i], vf);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(pw, ok[i] ? vf[e] : 0.f, acc[e]);
+        }
+        m = mn;
+    };
+
+    const int ngroups = (nunits + kKvUnits - 1) / kKvUnits;
+    if (ngroups > 0) issue(0, kb[0], vb[0]);
+    for (int g = 0; g < ngroups; g += 2) {
+        if (g + 1 < ngroups) issue(g + 1, kb[1], vb[1]);
+        consume(g, kb[0], vb[0]);
+        if (g + 2 < ngroups) issue(g + 2, kb[0], vb[0]);
+        if (g + 1 < ngroups) consume(g + 1, kb[1], vb[1]);
+    }
+
+    // combine the lane groups: LDS [G] m, [G] l, [G][HD] acc
+    float* gm = (float*)lds;
+    float* gl = gm + G;
+    float* ga = gl + G;
+    const int grp = w * RPL + lane / LPR;
+    if (lane % LPR == 0) { gm[grp] = m; gl[grp] = l; }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) ga[grp * HD + c0 + e] = acc[e];
+    __syncthreads();
+    if (tid < HD) {
+        float M = kSentinel;
+        for (int g = 0; g < G; ++g) M = fmaxf(M, gm[g]);
+        float L = 0.f, A = 0.f;
+        for (int g = 0; g < G; ++g) {
+            const float wgt = fast_exp2(gm[g] - M);
+            L = fmaf(gl[g], wgt, L);
+            A = fmaf(ga[g * HD + tid], wgt, A);
+        }
+        const int32_t* split_count = p.plan + APT_PW_HEADER;
+        const int32_t* ws_offset = split_count + p.B;
+        const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.kv_chunk) * p.H + h;
+        p.ws_acc[slot * HD + tid] = A;
+        if (tid == 0) p.ws_ml[slot] = make_float2(M, L);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// hidden-kind item, plain-ALU version (fp32 configs and shapes the MFMA kernel
+// does not cover).  chunk <= 64 tokens.
+// ---------------------------------------------------------------------------------
+template <int DT, int HD>
+__device__ void hidden_item_valu(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+    constexpr int NG = kThreads / HD;     // token groups
+    constexpr int TJ = 4;                 // tokens per pass of a thread
+    constexpr int LD = HD + 1;
+    const int C = p.hidden_chunk;
+    float* Ks = (float*)lds;              // [C][LD]
+    float* Vs = Ks + C * LD;              // [C][LD]
+    float* sc = Vs + C * LD;              // [64]
+    float* red = sc + 64;                 // [2]
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c = tid % HD, g = tid / HD;
+    const int n = t1 - t0;
+    const int d = p.d;
+    const int64_t blk_elems = (int64_t)p.bs * d;
+
+    const float bk = load_elem<DT>(p.b_K, (int64_t)h * HD + c);
+    const float bv = load_elem<DT>(p.b_V, (int64_t)h * HD + c);
+    for (int j0 = g * TJ; j0 < n; j0 += NG * TJ) {
+        int64_t xoff[TJ];
+#pragma unroll
+        for (int t = 0; t < TJ; ++t) {
+            int tok = t0 + j0 + t;
+            tok = tok < t1 ? tok : t1 - 1;
+            const int64_t blk = p.block_tables[(int64_t)r * 2 * p.max_blocks + (tok >> p.log2_bs)];
+            xoff[t] = blk * blk_elems + (int64_t)(tok & (p.bs - 1)) * d;
+        }
+        float ak[TJ], av[TJ];
+#pragma unroll
+        for (int t = 0; t < TJ; ++t) { ak[t] = bk; av[t] = bv; }
+        for (int i = 0; i < d; ++i) {
+            const float wk = load_elem<DT>(p.W_K, (int64_t)i * d + (int64_t)h * HD + c);
+            const float wv = load_elem<DT>(p.W_V, (int64_t)i * d + (int64_t)h * HD + c);
+#pragma unroll
+            for (int t = 0; t < TJ; ++t) {
+                const float x = load_elem<DT>(p.hidden_pages, xoff[t] + i);
+                ak[t] = fmaf(x, wk, ak[t]);
+                av[t] = fmaf(x, wv, av[t]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TJ; ++t)
+            if (j0 + t < n) { Ks[(j0 + t) * LD + c] = ak[t]; Vs[(j0 + t) * LD + c] = av[t]; }
+    }
+    __syncthreads();
+    for (int j = tid; j < n; j += kThreads) {
+        float s = 0.f;
+        for (int cc = 0; cc < HD; ++cc)
+            s = fmaf(Ks[j * LD + cc], load_elem<DT>(p.q, ((int64_t)r * p.H + h) * HD + cc), s);
+        sc[j] = s * p.scale_log2e;
+    }
+    __syncthreads();
+    if (w == 0) {
+        const float v = lane < n ? sc[lane] : kSentinel;
+        const float m = group_max<64>(v);
+        const float pw = lane < n ? fast_exp2(v - m) : 0.f;
+        const float l = group_sum<64>(pw);
+        sc[lane] = pw;
+        if (lane == 0) { red[0] = m; red[1] = l; }
+    }
+    __syncthreads();
+    if (tid < HD) {
+        float a = 0.f;
+        for (int j = 0; j < n; ++j) a = fmaf(sc[j], Vs[j * LD + tid], a);
+        const int32_t* split_count = p.plan + APT_PW_HEADER;
+        const int32_t* ws_offset = split_count + p.B;
+        const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.hidden_chunk) * p.H + h;
+        p.ws_acc[slot * HD + tid] = a;
+        if (tid == 0) p.ws_ml[slot] = make_float2(red[0], red[1]);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// hidden-kind item, MFMA version (fp16 / bf16, head_dim 128)
+// ---------------------------------------------------------------------------------
+// Per item: D[256 channels][256 tokens] = Wp_h[256][d] * X^T[d][256], channels 0..127 = K_h,
+// 128..255 = V_h.  Wave (mat, th) owns channels mat*128.. and tokens th*128.. as 4x4 tiles
+// of v_mfma_f32_32x32x16.  k runs in tiles of 64 through a double-buffered LDS stage:
+// per buffer 32 KB of packed weights (already in LDS order in memory) and 32 KB of X rows.
+// Rows are 128 B; the 16-byte unit c of a row sits at c ^ swz(row), which keeps both the
+// row-wise writes and the column-wise MFMA operand reads spread over all banks.
+constexpr int kBK = 64;
+constexpr int kTileBytes = 256 * kBK * 2;              // 32 KB
+constexpr int kStageBytes = 2 * kTileBytes;            // W tile + X tile
+constexpr int kMfmaLds = 2 * kStageBytes;              // 128 KB
+
+__host__ __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+
+template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
+    if constexpr (DT == 1)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8_t, a), __builtin_bit_cast(h8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
+}
+
+template <int DT>
+__device__ void hidden_item_mfma(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+    constexpr int HD = 128;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int mat = w >> 1, th = w & 1;
+    const int d = p.d;
+    const int nkt = d / kBK;
+    const int64_t blk_bytes = (int64_t)p.bs * d * 2;
+
+    // global sources.  X: thread -> 16-byte unit (tid & 7) of rows (tid >> 3) + 32 i
+    const char* xsrc[8];
+    const int xu = tid & 7, xr0 = tid >> 3;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int tok = t0 + xr0 + 32 * i;
+        tok = tok < t1 ? tok : t1 - 1;          // rows past the range repeat the last token (masked later)
+        const int64_t blk = p.block_tables[(int64_t)r * 2 * p.max_blocks + (tok >> p.log2_bs)];
+        xsrc[i] = p.hidden_pages + blk * blk_bytes + ((int64_t)(tok & (p.bs - 1)) * d) * 2 + xu * 16;
+    }
+    const int xdst = xr0 * 128 + ((xu ^ swz(xr0)) * 16);          // + i * 32 rows * 128 B; swz(row + 32 i) = swz(row) ^ (4 i & 7)
+    const char* wsrc = p.W_packed + (int64_t)h * nkt * kTileBytes + tid * 16;
+
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    uint4 xr[8], wr[8];
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wr[i] = *(const uint4*)(wsrc + (int64_t)kt * kTileBytes + i * 4096);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) xr[i] = *(const uint4*)(xsrc[i] + kt * (kBK * 2));
+    };
+    auto lstore = [&](int buf) {
+        char* wb = lds + buf * kStageBytes;
+        char* xb = wb + kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(uint4*)(wb + tid * 16 + i * 4096) = wr[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = xr0 + 32 * i;
+            *(uint4*)(xb + row * 128 + ((xu ^ swz(row)) * 16)) = xr[i];
+        }
+    };
+    (void)xdst;
+
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    const int arow = mat * 128 + (lane & 31);
+    const int brow = th * 128 + (lane & 31);
+    for (int kt = 0; kt < nkt; ++kt) {
+        if (kt + 1 < nkt) gload(kt + 1);
+        const char* wb = lds + (kt & 1) * kStageBytes;
+        const char* xb = wb + kTileBytes;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int kc = 2 * ks + (lane >> 5);
+            uint4 af[4], bf[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const int row = arow + 32 * a;
+                af[a] = *(const uint4*)(wb + row * 128 + ((kc ^ swz(row)) * 16));
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int row = brow + 32 * b;
+                bf[b] = *(const uint4*)(xb + row * 128 + ((kc ^ swz(row)) * 16));
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] = mfma32<DT>(af[a], bf[b], acc[a][b]);
+        }
+        if (kt + 1 < nkt) lstore((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  acc[a][b][e] of lane: channel 32a + 8(e/4) + 4(lane/32) + e%4 of the
+    // wave's matrix, token th*128 + 32b + lane%32.
+    float* s_lds = (float*)lds;            // [256] scores
+    float* o_lds = s_lds + 256;            // [2][128] per-half un-normalised output
+    float* ml_lds = o_lds + 256;           // [2][2]
+    const int half = lane >> 5;
+    if (mat == 0) {
+        float qv[4][16];
+        float qb = 0.f;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int ch = 32 * a + 8 * (e >> 2) + 4 * half + (e & 3);
+                qv[a][e] = load_elem<DT>(p.q, ((int64_t)r * p.H + h) * HD + ch) * p.scale_log2e;
+                qb = fmaf(qv[a][e], load_elem<DT>(p.b_K, (int64_t)h * HD + ch), qb);
+            }
+        qb += __shfl_xor(qb, 32);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            float sp = 0.f;
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sp = fmaf(acc[a][b][e], qv[a][e], sp);
+            sp += __shfl_xor(sp, 32);
+            if (lane < 32) s_lds[th * 128 + 32 * b + lane] = sp + qb;
+        }
+    }
+    __syncthreads();
+    if (mat == 1) {
+        const int nvalid = t1 - t0;
+        float s[4], pw[4];
+        float m = kSentinel;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int tl = th * 128 + 32 * b + (lane & 31);
+            s[b] = tl < nvalid ? s_lds[tl] : kSentinel;
+            m = fmaxf(m, s[b]);
+        }
+        m = group_max<32>(m);
+        float l = 0.f;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int tl = th * 128 + 32 * b + (lane & 31);
+            pw[b] = tl < nvalid ? fast_exp2(s[b] - m) : 0.f;
+            l += pw[b];
+        }
+        l = group_sum<32>(l);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float o = 0.f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) o = fmaf(pw[b], acc[a][b][e], o);
+                o = group_sum<32>(o);
+                const int ch = 32 * a + 8 * (e >> 2) + 4 * half + (e & 3);
+                if ((lane & 31) == 0) o_lds[th * 128 + ch] = fmaf(l, load_elem<DT>(p.b_V, (int64_t)h * HD + ch), o);
+            }
+        if (lane == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
+    }
+    __syncthreads();
+    if (tid < HD) {
+        const float m0 = ml_lds[0], l0 = ml_lds[1], m1 = ml_lds[2], l1 = ml_lds[3];
+        const float M = fmaxf(m0, m1);
+        const float w0 = fast_exp2(m0 - M), w1 = fast_exp2(m1 - M);
+        const int32_t* split_count = p.plan + APT_PW_HEADER;
+        const int32_t* ws_offset = split_count + p.B;
+        const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.hidden_chunk) * p.H + h;
+        p.ws_acc[slot * HD + tid] = o_lds[tid] * w0 + o_lds[128 + tid] * w1;
+        if (tid == 0) p.ws_ml[slot] = make_float2(M, l0 * w0 + l1 * w1);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// the items kernel.  HIMPL: 0 = no hidden-kind items in the plan, 1 = plain ALU, 2 = MFMA
+// ---------------------------------------------------------------------------------
+template <int DT, int HD, int HIMPL>
+__global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
+    extern __shared__ __align__(16) char lds[];
+    const int item = blockIdx.x;
+    if (item >= p.n_items) return;
+    const int4 it = ((const int4*)(p.plan + p.items_off))[item];
+    if (item < p.n_hidden_items) {
+        if constexpr (HIMPL == 1) hidden_item_valu<DT, HD>(p, it.x, it.y, it.z, it.w, lds);
+        if constexpr (HIMPL == 2) hidden_item_mfma<DT>(p, it.x, it.y, it.z, it.w, lds);
+    } else {
+        kv_item<DT, HD>(p, it.x, it.y, it.z, it.w, lds);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// merge kernel: out[r][h][c] = sum_s acc_s[c] 2^(m_s - M) / sum_s l_s 2^(m_s - M)
+// ---------------------------------------------------------------------------------
+template <int ODT>
+__global__ __launch_bounds__(kThreads) void apt_merge_kernel(const int32_t* plan, const float* ws_acc, const float2* ws_ml,
+                                                             char* out, int B, int H, int HD) {
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= (int64_t)B * H * HD) return;
+    const int c = (int)(gid % HD);
+    const int64_t pair = gid / HD;
+    const int h = (int)(pair % H), r = (int)(pair / H);
+    const int32_t* split_count = plan + APT_PW_HEADER;
+    const int32_t* ws_offset = split_count + B;
+    const int ns = split_count[r];
+    const int64_t base = (int64_t)ws_offset[r] * H + h;
+    float M = kSentinel;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, ws_ml[base + (int64_t)s * H].x);
+    float L = 0.f, A = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const int64_t slot = base + (int64_t)s * H;
+        const float2 ml = ws_ml[slot];
+        const float wgt = fast_exp2(ml.x - M);
+        L = fmaf(ml.y, wgt, L);
+        A = fmaf(ws_acc[slot * HD + c], wgt, A);
+    }
+    const float o = A / L;
+    if constexpr (ODT == 0) ((float*)out)[gid] = o;
+    else if constexpr (ODT == 1) ((_Float16*)out)[gid] = (_Float16)o;
+    else ((uint16_t*)out)[gid] = f32_to_bf16_rne(o);
+}
+
+// ---------------------------------------------------------------------------------
+// weight packing for the MFMA kernel (one-off per layer)
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void apt_pack_kernel(const uint16_t* W_K, const uint16_t* W_V, uint4* packed,
+                                                            int d, int H) {
+    // one thread per 16-byte unit; consecutive threads take consecutive channels so
+    // that the strided reads of W coalesce
+    const int nkt = d / kBK;
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t total = (int64_t)H * nkt * 256 * 8;
+    if (gid >= total) return;
+    const int row = (int)(gid % 256);
+    const int c = (int)((gid / 256) % 8);
+    const int kt = (int)((gid / 2048) % nkt);
+    const int h = (int)(gid / (2048 * (int64_t)nkt));
+    const uint16_t* W = row < 128 ? W_K : W_V;
+    const int ch = h * 128 + (row & 127);
+    const int k0 = kt * kBK + c * 8;
+    uint16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = W[(int64_t)(k0 + e) * d + ch];
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16);
+    o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16);
+    o.w = v[6] | ((uint32_t)v[7] << 16);
+    packed[((int64_t)h * nkt + kt) * 2048 + row * 8 + (c ^ swz(row))] = o;
+}
+
+__global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const uint4* src, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------
+template <int DT, int HD, int HIMPL>
+int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
+    auto kern = apt_items_kernel<DT, HD, HIMPL>;
+    static bool attr_done = false;
+    if (lds_bytes > 64 * 1024 && !attr_done) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return APT_EHIP;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(p.n_items), dim3(kThreads), lds_bytes, st, p);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+template <int DT, int HD>
+int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
+    constexpr int EB = Elt<DT>::bytes;
+    constexpr int LPR = HD * EB / 16;
+    constexpr int G = 4 * (64 / LPR);
+    const size_t kv_lds = (size_t)(2 * G + G * HD) * 4;
+    if (p.n_hidden_items == 0) return launch_items<DT, HD, 0>(p, kv_lds, st);
+    if (himpl == APT_HIDDEN_VALU) {
+        size_t v = (size_t)(2 * p.hidden_chunk * (HD + 1) + 64 + 2) * 4;
+        return launch_items<DT, HD, 1>(p, v > kv_lds ? v : kv_lds, st);
+    }
+    if constexpr (DT != 0 && HD == 128) {
+        return launch_items<DT, HD, 2>(p, kMfmaLds, st);
+    }
+    return APT_ESHAPE;
+}
+
+}  // namespace
+
+extern "C" int apt_plan_upload(const void* plan_host, void* plan_dev, void* stream) {
+    apt_plan_info info;
+    int rc = apt_plan_get_info(plan_host, &info);
+    if (rc) return rc;
+    if (!plan_dev) return APT_EINVAL;
+    if (hipMemcpyAsync(plan_dev, plan_host, info.plan_bytes, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
+        return APT_EHIP;
+    return APT_OK;
+}
+
+extern "C" int apt_packed_weight_bytes(const apt_shape* s, size_t* bytes) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (!bytes) return APT_EINVAL;
+    *bytes = (size_t)2 * rs.s.d_model * rs.s.d_model * rs.elem_bytes;
+    return APT_OK;
+}
+
+extern "C" int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void* packed, void* stream) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (!W_K || !W_V || !packed) return APT_EINVAL;
+    if (rs.s.hidden_impl != APT_HIDDEN_MFMA) return APT_ESHAPE;
+    const int d = rs.s.d_model, H = rs.s.n_heads;
+    const int64_t total = (int64_t)H * (d / kBK) * 2048;
+    const int64_t blocks = (total + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(apt_pack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                       (const uint16_t*)W_K, (const uint16_t*)W_V, (uint4*)packed, d, H);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || bytes == 0 || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return APT_EINVAL;
+    const int64_t n = (int64_t)(bytes / 16);
+    int64_t blocks = (n + kThreads - 1) / kThreads;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(apt_copy_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                       (uint4*)dst, (const uint4*)src, n);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
+                                      const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                      const void* W_K, const void* W_V, const void* W_packed,
+                                      const void* b_K, const void* b_V, const int32_t* block_tables,
+                                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (!plan_host || !plan_dev || !q || !block_tables || !out || !workspace) return APT_EINVAL;
+    const int32_t* pw = (const int32_t*)plan_host;
+    if (pw[APT_PW_MAGIC] != APT_PLAN_MAGIC) return APT_EINVAL;
+    // the plan must have been made for this shape
+    if (pw[APT_PW_HEADS] != rs.s.n_heads || pw[APT_PW_HEAD_DIM] != rs.s.head_dim || pw[APT_PW_HCHUNK] != rs.s.hidden_chunk ||
+        pw[APT_PW_KCHUNK] != rs.s.kv_chunk || pw[APT_PW_HIMPL] != rs.s.hidden_impl)
+        return APT_ESHAPE;
+    const int n_items = pw[APT_PW_NITEMS], n_hidden = pw[APT_PW_NHIDDEN];
+    const int B = pw[APT_PW_BATCH];
+    const uint64_t need = apt_ws_bytes(pw[APT_PW_NPARTIALS], rs.s.n_heads, rs.s.head_dim);
+    if (workspace_bytes < need) return APT_EWORKSPACE;
+    if (((uintptr_t)workspace & 15) != 0) return APT_EINVAL;
+    if (n_hidden < n_items && (!k_pages || !v_pages)) return APT_EINVAL;
+    if (n_hidden > 0) {
+        if (!hidden_pages || !b_K || !b_V) return APT_EINVAL;
+        if (rs.s.hidden_impl == APT_HIDDEN_MFMA && !W_packed) return APT_EINVAL;
+        if (rs.s.hidden_impl == APT_HIDDEN_VALU && (!W_K || !W_V)) return APT_EINVAL;
+    }
+    int log2_bs = 0;
+    while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
+
+    ItemParams p;
+    p.plan = (const int32_t*)plan_dev;
+    p.q = (const char*)q;
+    p.k_pages = (const char*)k_pages;
+    p.v_pages = (const char*)v_pages;
+    p.hidden_pages = (const char*)hidden_pages;
+    p.W_K = (const char*)W_K;
+    p.W_V = (const char*)W_V;
+    p.W_packed = (const char*)W_packed;
+    p.b_K = (const char*)b_K;
+    p.b_V = (const char*)b_V;
+    p.block_tables = block_tables;
+    const int64_t n_slots = (int64_t)pw[APT_PW_NPARTIALS] * rs.s.n_heads;
+    p.ws_acc = (float*)workspace;
+    p.ws_ml = (float2*)((float*)workspace + n_slots * rs.s.head_dim);
+    p.B = B; p.H = rs.s.n_heads; p.d = rs.s.d_model; p.bs = rs.s.block_size; p.log2_bs = log2_bs;
+    p.max_blocks = rs.s.max_blocks_per_req;
+    p.n_items = n_items; p.n_hidden_items = n_hidden;
+    p.hidden_chunk = rs.s.hidden_chunk; p.kv_chunk = rs.s.kv_chunk; p.items_off = pw[APT_PW_ITEMS_OFF];
+    p.scale_log2e = rs.s.softmax_scale * 1.4426950408889634f;
+    hipStream_t st = (hipStream_t)stream;
+
+    const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;
+    if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, st);
+    else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, st);
+    else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, st);
+    else if (dt == APT_F16 && hd == 128) rc = launch_items_impl<1, 128>(p, hi, st);
+    else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, st);
+    else rc = launch_items_impl<2, 128>(p, hi, st);
+    if (rc) return rc;
+
+    const int64_t total = (int64_t)B * rs.s.n_heads * hd;
+    const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
+    if (rs.s.out_dtype == APT_F32)
+        hipLaunchKernelGGL(apt_merge_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+    else if (rs.s.out_dtype == APT_F16)
+        hipLaunchKernelGGL(apt_merge_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+    else
+        hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}

@@ -1,0 +1,93 @@
+"""Device-side plumbing around the C-ABI calls: holds the torch buffers of one batch
+(plan, cache maps, workspace, output) and of one layer (pool, weights, q) and issues
+the library calls.  Memory and streams only; no arithmetic happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as ab
+from . import workloads as wl
+
+_TORCH_OUT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _to_dev(raw: np.ndarray, device) -> torch.Tensor:
+    """Upload a raw storage array byte for byte (16-bit types travel as int16)."""
+    a = np.ascontiguousarray(raw)
+    if a.dtype in (np.uint16, np.float16):
+        a = a.view(np.int16)
+    return torch.from_numpy(a).to(device)
+
+
+class DeviceLayer:
+    def __init__(self, runner: "DecodeRunner", layer: wl.Layer, separate_pools: bool = False):
+        dev = runner.device
+        self.pool = _to_dev(layer.pool, dev)
+        if separate_pools:
+            self.k_pool, self.v_pool = self.pool.clone(), self.pool.clone()
+        else:
+            self.k_pool = self.v_pool = self.pool      # one unified pool
+        self.W_K = _to_dev(layer.W_K, dev)
+        self.W_V = _to_dev(layer.W_V, dev)
+        self.b_K = _to_dev(layer.b_K, dev)
+        self.b_V = _to_dev(layer.b_V, dev)
+        self.q = _to_dev(layer.q, dev)
+        self.W_packed = None
+        if runner.info.hidden_impl == ab.APT_HIDDEN_MFMA:
+            nbytes = ab.apt_packed_weight_bytes(runner.shape)
+            self.W_packed = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            ab.apt_pack_weights(runner.shape, self.W_K, self.W_V, self.W_packed,
+                                torch.cuda.current_stream(dev).cuda_stream)
+
+
+class DecodeRunner:
+    """One batch: plan + cache maps + workspace + output buffer on the device."""
+
+    def __init__(self, batch: wl.Batch, out_dtype: str = "f32", hidden_impl: int = ab.APT_HIDDEN_AUTO,
+                 hidden_chunk: int = 0, kv_chunk: int = 0, device: str = "cuda:0", scale=None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required: there is no CPU path")
+        cfg = batch.cfg
+        self.batch, self.cfg = batch, cfg
+        self.device = torch.device(device)
+        self.out_dtype = out_dtype
+        self.shape = ab.make_shape(cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.block_size, cfg.dtype,
+                                   batch.max_blocks, cfg.softmax_scale if scale is None else scale,
+                                   out_dtype=out_dtype, hidden_chunk=hidden_chunk, kv_chunk=kv_chunk,
+                                   hidden_impl=hidden_impl)
+        max_ctx = batch.max_blocks * cfg.block_size
+        nbytes = ab.apt_plan_max_bytes(self.shape, batch.B, max_ctx)
+        self.plan_host = torch.empty(nbytes // 4, dtype=torch.int32, pin_memory=True)
+        self.plan_dev = torch.empty(nbytes // 4, dtype=torch.int32, device=self.device)
+        self.block_tables = torch.from_numpy(batch.block_tables).to(self.device)
+        self.out = torch.empty((batch.B, cfg.n_heads, cfg.head_dim), dtype=_TORCH_OUT[out_dtype], device=self.device)
+        self.info = None
+        self.workspace = None
+        self.plan()
+
+    def stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def plan(self):
+        """a1: partition on the host, copy the blob to the device."""
+        self.info = ab.apt_plan(self.shape, self.batch.ctx_lens, self.batch.cache_kind, self.plan_host)
+        ab.apt_plan_upload(self.plan_host, self.plan_dev, self.stream())
+        need = int(self.info.workspace_bytes)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=self.device)
+        return self.info
+
+    def upload(self, layer: wl.Layer, separate_pools: bool = False) -> DeviceLayer:
+        return DeviceLayer(self, layer, separate_pools)
+
+    def run(self, dl: DeviceLayer) -> torch.Tensor:
+        """a2-a4: the attention call for one layer (asynchronous on the current stream)."""
+        ab.apt_hybrid_decode_attn(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool, dl.pool,
+                                  dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables, self.out,
+                                  self.workspace, self.workspace.numel(), self.stream())
+        return self.out
+
+    def out_f64(self) -> np.ndarray:
+        torch.cuda.synchronize(self.device)
+        return self.out.float().cpu().numpy().astype(np.float64)

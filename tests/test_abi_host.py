@@ -1,0 +1,135 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, the
+host planner matches the plain partition rule bit for bit, and bad arguments are turned
+into error codes.  No device call is made here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import plan_oracle as po
+from paper_2504_07494_amd import binding as ab
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _shape(**kw):
+    base = dict(d_model=5120, n_heads=40, head_dim=128, block_size=16, dtype="f16", max_blocks_per_req=128,
+                softmax_scale=128 ** -0.5)
+    base.update(kw)
+    return ab.make_shape(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "apt_hybrid.h")).read()
+    declared = set(re.findall(r"\b(apt_[a-z_0-9]+)\s*\(", header))
+    declared -= {"apt_status"}
+    assert declared == set(ab.EXPORTS), declared ^ set(ab.EXPORTS)
+    lib = ab.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert ab.apt_version() >= 100
+    assert ab.apt_strerror(0) == "ok" and "shape" in ab.apt_strerror(ab.APT_ESHAPE)
+
+
+def _plan(shape, lens, kinds):
+    lens = np.asarray(lens, dtype=np.int32)
+    kinds = np.asarray(kinds, dtype=np.uint8)
+    nbytes = ab.apt_plan_max_bytes(shape, len(lens), int(lens.max()))
+    buf = np.full(nbytes // 4, -7, dtype=np.int32)
+    info = ab.apt_plan(shape, lens, kinds, buf)
+    return buf, info
+
+
+@pytest.mark.parametrize("seed,B,lo,hi,ratio", [(0, 64, 128, 2048, 0.5), (1, 1, 1, 1, 1.0), (2, 33, 1, 700, 0.3),
+                                                (3, 256, 64, 2048, 0.0), (4, 17, 255, 258, 1.0)])
+def test_plan_is_bit_exact_against_the_rule(seed, B, lo, hi, ratio):
+    g = np.random.default_rng(seed)
+    lens = g.integers(lo, hi + 1, size=B)
+    kinds = (g.random(B) < ratio).astype(np.uint8)
+    shape = _shape()
+    buf, info = _plan(shape, lens, kinds)
+    got = ab.decode_plan(buf)
+    want = po.plan(lens, kinds, 40, info.hidden_chunk, info.kv_chunk)
+    assert got == want
+    assert info.n_items == len(want["items"]) and info.n_hidden_items == want["n_hidden_items"]
+    assert info.n_partials == want["n_partials"]
+    assert info.total_tokens == int(lens.sum()) and info.hidden_tokens == int(lens[kinds == 1].sum())
+    assert info.workspace_bytes == want["n_partials"] * 40 * (128 + 2) * 4
+    assert info.hidden_impl == ab.APT_HIDDEN_MFMA and info.hidden_chunk == 256
+    # deterministic bytes
+    buf2, _ = _plan(shape, lens, kinds)
+    assert np.array_equal(buf[:info.plan_bytes // 4], buf2[:info.plan_bytes // 4])
+
+
+def test_plan_with_explicit_chunks_and_small_heads():
+    shape = _shape(d_model=256, n_heads=4, head_dim=64, dtype="f32", max_blocks_per_req=8, hidden_chunk=8, kv_chunk=32)
+    lens, kinds = [16, 128, 1, 77], [1, 0, 1, 0]
+    buf, info = _plan(shape, lens, kinds)
+    assert info.hidden_impl == ab.APT_HIDDEN_VALU
+    assert ab.decode_plan(buf) == po.plan(lens, kinds, 4, 8, 32)
+
+
+def test_plan_rejects_bad_arguments():
+    shape = _shape()
+    buf = np.zeros(1 << 16, dtype=np.int32)
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_plan(shape, np.array([0], dtype=np.int32), np.array([0], dtype=np.uint8), buf)
+    assert e.value.status == ab.APT_EINVAL
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_plan(shape, np.array([5], dtype=np.int32), np.array([2], dtype=np.uint8), buf)
+    assert e.value.status == ab.APT_EINVAL
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_plan(shape, np.array([128 * 16 + 1], dtype=np.int32), np.array([0], dtype=np.uint8), buf)
+    assert e.value.status == ab.APT_ERANGE
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_plan(shape, np.array([2048] * 8, dtype=np.int32), np.array([1] * 8, dtype=np.uint8), buf[:64])
+    assert e.value.status == ab.APT_EWORKSPACE
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_heads=39), ab.APT_ESHAPE),                 # H * hd != d
+    (dict(head_dim=96, n_heads=40, d_model=3840), ab.APT_ESHAPE),
+    (dict(block_size=12), ab.APT_ESHAPE),
+    (dict(hidden_chunk=128), ab.APT_ESHAPE),           # the MFMA tile is 256 tokens
+    (dict(kv_chunk=100), ab.APT_ESHAPE),               # not a multiple of the block size
+    (dict(dtype="f32", hidden_impl=ab.APT_HIDDEN_MFMA), ab.APT_ESHAPE),
+    (dict(dtype="f16", out_dtype="bf16"), ab.APT_EDTYPE),
+])
+def test_shape_validation(kw, status):
+    shape = _shape(**kw)
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_plan_max_bytes(shape, 4, 100)
+    assert e.value.status == status
+
+
+def test_validate_host_range_checks_block_ids():
+    shape = _shape(max_blocks_per_req=4)
+    lens = np.array([20, 33], dtype=np.int32)
+    kinds = np.array([0, 1], dtype=np.uint8)
+    bt = np.full((2, 2, 4), -1, dtype=np.int32)
+    bt[0, 0, :2] = [0, 1]; bt[0, 1, :2] = [2, 3]; bt[1, 0, :3] = [4, 5, 6]
+    ab.apt_validate_host(shape, lens, kinds, bt, 7)
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_validate_host(shape, lens, kinds, bt, 6)
+    assert e.value.status == ab.APT_ERANGE
+    bt[0, 1, 1] = -1
+    with pytest.raises(ab.AptError):
+        ab.apt_validate_host(shape, lens, kinds, bt, 7)
+
+
+def test_attention_call_rejects_bad_arguments_before_any_launch():
+    # null pointers and a foreign plan are caught on the host (no device is touched)
+    shape = _shape()
+    buf, info = _plan(shape, [300], [0])
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn(shape, buf, None, None, None, None, None, None, None, None, None, None, None,
+                                  None, None, 0)
+    assert e.value.status == ab.APT_EINVAL
+    other = _shape(kv_chunk=256)
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn(other, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 1 << 30)
+    assert e.value.status == ab.APT_ESHAPE
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn(shape, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 8)
+    assert e.value.status == ab.APT_EWORKSPACE

@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid-cache decode attention step on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W [--config opt13b] [--hidden-ratio R]
+
+A step is one pass of the whole hot path for one layer over one synthetic batch whose
+inputs are already resident in HBM: the ragged work partition (host planner + copy of the
+plan to the device), the item kernel (paged-KV attention and hidden-cache recompute +
+attention in one launch) and the merge kernel.  The metric is cached tokens per second
+per decode layer = sum of the batch's context lengths / time per step.
+
+Prints ONE JSON line.  `roofline` describes the item kernel, timed with HIP events
+recorded around it on its launch stream inside the timed region.  `cpu_baseline` is the
+CPU oracle timed on this machine's host cores over a bounded random sample of (request,
+head) pairs of the same batch (it is a baseline, not a target); the same sample is used
+to check the GPU output.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
+
+
+class HipEvents:
+    """Pairs of raw HIP events (created through the HIP runtime that torch has loaded)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        assert rc == 0, rc
+        return ms.value
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def read_traffic(workload_key):
+    """HBM bytes per item-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE, scaled by a copy kernel of known size), kept as text under profiles/."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        t = line.split()
+        if len(t) >= 2 and t[0] == workload_key:
+            try:
+                return float(t[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="opt13b")
+    ap.add_argument("--hidden-ratio", type=float, default=None)
+    ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pairs-per-thread", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2504_07494_amd import workloads as wl
+    from paper_2504_07494_amd.harness import DecodeRunner
+
+    cfg = wl.CONFIGS[args.config]
+    if args.hidden_ratio is not None:
+        cfg = wl.with_ratio(cfg, args.hidden_ratio)
+    t_gen = time.time()
+    batch = wl.make_batch(cfg)
+    layer = wl.make_layer(batch, workers=min(16, os.cpu_count() or 8))
+    t_gen = time.time() - t_gen
+
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk)
+    dl = rn.upload(layer)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        rn.plan()
+        rn.run(dl)
+    torch.cuda.synchronize()
+
+    ev = HipEvents(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        rn.plan()
+        rn.run(dl, ev.pairs[i][0], ev.pairs[i][1])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    ev.close()
+    kern_avg_ms = float(np.mean(kern_ms))
+
+    total_tokens = batch.total_tokens
+    hidden_tokens = batch.hidden_tokens
+    kv_tokens = batch.kv_tokens
+    d, e = cfg.d_model, wl.ELEM_BYTES[cfg.dtype]
+    value = total_tokens / (ms_per_step * 1e-3)
+
+    # algorithmic work of the item kernel per launch
+    flops = 4.0 * d * d * hidden_tokens                 # K and V projections of hidden-kind tokens
+    kv_bytes = 2.0 * d * e * kv_tokens                  # K row + V row of KV-kind tokens
+    hid_bytes = 1.0 * d * e * hidden_tokens
+    t_mfma = flops / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)
+    t_hbm = (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
+    wkey = f"{cfg.name}@{cfg.hidden_ratio:g}"
+    if t_mfma >= t_hbm:
+        ach = flops / (kern_avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
+                "frac": ach / PEAK_MFMA_TFLOPS[cfg.dtype], "traffic": read_traffic(wkey)}
+    else:
+        ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey)}
+    roof.update({"kernel": "apt_items_kernel", "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
+                 "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
+
+    result = {
+        "metric": "cached tokens/sec per decode layer; HBM GB/s and MFMA util vs MI355X peak",
+        "value": value, "unit": "cached tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: d_model={d}, {cfg.n_heads} heads x {cfg.head_dim}, {cfg.dtype}, "
+                               f"batch {batch.B}, ctx {cfg.len_dist}[{cfg.len_lo},{cfg.len_hi}], block {cfg.block_size}, "
+                               f"{int(round(100 * cfg.hidden_ratio))}% hidden-cache requests",
+                   "total_tokens": total_tokens, "hidden_tokens": hidden_tokens, "kv_tokens": kv_tokens,
+                   "n_items": int(rn.info.n_items), "n_hidden_items": int(rn.info.n_hidden_items),
+                   "seed": cfg.seed, "input_gen_s": round(t_gen, 2)},
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as o
+        nthreads = o.threads()
+        g = np.random.default_rng(cfg.seed)
+        n_pairs = min(batch.B * cfg.n_heads, args.pairs_per_thread * nthreads)
+        flat = g.choice(batch.B * cfg.n_heads, size=n_pairs, replace=False)
+        pairs = np.stack([flat // cfg.n_heads, flat % cfg.n_heads], axis=1).astype(np.int32)
+        sh = o.shape_of(d, cfg.n_heads, cfg.head_dim, cfg.block_size, cfg.dtype, batch.max_blocks, cfg.softmax_scale)
+        tc = time.perf_counter()
+        want = o.attn(sh, layer.q, layer.pool, layer.pool, layer.pool, layer.W_K, layer.b_K, layer.W_V, layer.b_V,
+                      batch.block_tables, batch.ctx_lens, batch.cache_kind, pairs=pairs)
+        tc = time.perf_counter() - tc
+        tok_equiv = float(batch.ctx_lens[pairs[:, 0]].astype(np.int64).sum()) / cfg.n_heads
+        got = rn.out_f64()[pairs[:, 0], pairs[:, 1]]
+        err = np.abs(got - want)
+        big = np.abs(want) >= 1e-2
+        result["cpu_baseline"] = {
+            "value": tok_equiv / tc, "unit": "cached tokens/s", "cores": nthreads, "kind": "oracle",
+            "sample": f"{n_pairs} random (request, head) pairs of the same batch = {tok_equiv:.0f} token-equivalents "
+                      f"in {tc:.1f} s, extrapolated",
+        }
+        result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
+                                   "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

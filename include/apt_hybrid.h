@@ -192,6 +192,19 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same step as apt_hybrid_decode_attn (Eq. 1-3 over both cache kinds); in addition
+ * the HIP events ev_begin and ev_end (hipEvent_t handles created by the caller with
+ * timing enabled; either may be NULL) are recorded on `stream` immediately before and
+ * after the item kernel, so that a caller can time that kernel apart from the merge.
+ */
+int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, const void* plan_dev,
+                                 const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                 const void* W_K, const void* W_V, const void* W_packed,
+                                 const void* b_K, const void* b_V, const int32_t* block_tables,
+                                 void* out, void* workspace, size_t workspace_bytes, void* stream,
+                                 void* ev_begin, void* ev_end);
+
+/*
  * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16; device
  * pointers, 16-byte aligned).  Exists so that hardware traffic counters can be
  * calibrated against a kernel of known traffic (reads `bytes`, writes `bytes`).

@@ -22,7 +22,7 @@ DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 
 EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt_plan_get_info", "apt_plan_upload",
            "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
-           "apt_copy_bytes"]
+           "apt_hybrid_decode_attn_timed", "apt_copy_bytes"]
 
 
 class apt_shape(C.Structure):
@@ -143,6 +143,16 @@ def apt_hybrid_decode_attn(shape, plan_host, plan_dev, q, k_pages, v_pages, hidd
                                         _ptr(v_pages), _ptr(hidden_pages), _ptr(W_K), _ptr(W_V), _ptr(W_packed),
                                         _ptr(b_K), _ptr(b_V), _ptr(block_tables), _ptr(out), _ptr(workspace),
                                         C.c_size_t(workspace_bytes), C.c_void_p(stream)), "apt_hybrid_decode_attn")
+
+
+def apt_hybrid_decode_attn_timed(shape, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed,
+                                 b_K, b_V, block_tables, out, workspace, workspace_bytes, stream, ev_begin, ev_end):
+    """ev_begin / ev_end: raw hipEvent_t handles (int) or None."""
+    _check(lib().apt_hybrid_decode_attn_timed(C.byref(shape), _ptr(plan_host), _ptr(plan_dev), _ptr(q),
+                                              _ptr(k_pages), _ptr(v_pages), _ptr(hidden_pages), _ptr(W_K), _ptr(W_V),
+                                              _ptr(W_packed), _ptr(b_K), _ptr(b_V), _ptr(block_tables), _ptr(out),
+                                              _ptr(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream),
+                                              _ptr(ev_begin), _ptr(ev_end)), "apt_hybrid_decode_attn_timed")
 
 
 def apt_copy_bytes(dst, src, nbytes, stream=0):

@@ -660,11 +660,12 @@ extern "C" int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* st
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
-                                      const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
-                                      const void* W_K, const void* W_V, const void* W_packed,
-                                      const void* b_K, const void* b_V, const int32_t* block_tables,
-                                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, const void* plan_dev,
+                                            const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                            const void* W_K, const void* W_V, const void* W_packed,
+                                            const void* b_K, const void* b_V, const int32_t* block_tables,
+                                            void* out, void* workspace, size_t workspace_bytes, void* stream,
+                                            void* ev_begin, void* ev_end) {
     apt_resolved rs;
     int rc = apt_resolve(s, &rs);
     if (rc) return rc;
@@ -712,6 +713,7 @@ extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host,
     hipStream_t st = (hipStream_t)stream;
 
     const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;
+    if (ev_begin && hipEventRecord((hipEvent_t)ev_begin, st) != hipSuccess) return APT_EHIP;
     if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, st);
     else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, st);
     else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, st);
@@ -719,6 +721,7 @@ extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host,
     else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, st);
     else rc = launch_items_impl<2, 128>(p, hi, st);
     if (rc) return rc;
+    if (ev_end && hipEventRecord((hipEvent_t)ev_end, st) != hipSuccess) return APT_EHIP;
 
     const int64_t total = (int64_t)B * rs.s.n_heads * hd;
     const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
@@ -729,4 +732,13 @@ extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host,
     else
         hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
+                                      const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                      const void* W_K, const void* W_V, const void* W_packed,
+                                      const void* b_K, const void* b_V, const int32_t* block_tables,
+                                      void* out, void* workspace, size_t workspace_bytes, void* stream) {
+    return apt_hybrid_decode_attn_timed(s, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed,
+                                        b_K, b_V, block_tables, out, workspace, workspace_bytes, stream, nullptr, nullptr);
 }

@@ -81,11 +81,18 @@ class DecodeRunner:
     def upload(self, layer: wl.Layer, separate_pools: bool = False) -> DeviceLayer:
         return DeviceLayer(self, layer, separate_pools)
 
-    def run(self, dl: DeviceLayer) -> torch.Tensor:
-        """a2-a4: the attention call for one layer (asynchronous on the current stream)."""
-        ab.apt_hybrid_decode_attn(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool, dl.pool,
-                                  dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables, self.out,
-                                  self.workspace, self.workspace.numel(), self.stream())
+    def run(self, dl: DeviceLayer, ev_begin=None, ev_end=None) -> torch.Tensor:
+        """a2-a4: the attention call for one layer (asynchronous on the current stream).
+        ev_begin / ev_end: optional raw hipEvent_t handles recorded around the item kernel."""
+        if ev_begin is None and ev_end is None:
+            ab.apt_hybrid_decode_attn(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool, dl.pool,
+                                      dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables, self.out,
+                                      self.workspace, self.workspace.numel(), self.stream())
+        else:
+            ab.apt_hybrid_decode_attn_timed(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool,
+                                            dl.pool, dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables,
+                                            self.out, self.workspace, self.workspace.numel(), self.stream(),
+                                            ev_begin, ev_end)
         return self.out
 
     def out_f64(self) -> np.ndarray:

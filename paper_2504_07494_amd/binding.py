@@ -66,6 +66,8 @@ def _ptr(x):
     """Address of a torch tensor, numpy array, ctypes object or plain int (None -> NULL)."""
     if x is None:
         return C.c_void_p(None)
+    if isinstance(x, C.c_void_p):
+        return x
     if isinstance(x, int):
         return C.c_void_p(x)
     if isinstance(x, np.ndarray):

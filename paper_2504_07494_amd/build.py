@@ -15,7 +15,7 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            # packed-fp32 instruction forms are kept out of the device code
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
+           "-Wno-inline-asm", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", LIB]
     if verbose:

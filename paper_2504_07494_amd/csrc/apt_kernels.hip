@@ -342,27 +342,60 @@ template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4&
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
 }
 
+// 16-byte global -> LDS copy without a register stage: lane i's 16 bytes land at
+// lds_addr + 16 i.  The LDS address goes through M0 and must be wave-uniform.
+__device__ inline void gload_lds16(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
+}
+
 template <int DT>
 __device__ void hidden_item_mfma(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
     constexpr int HD = 128;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mat = w >> 1, th = w & 1;
     const int d = p.d;
-    const int nkt = d / kBK;
+    const int nkt = d / kBK;                 // even: d is a multiple of 128
     const int64_t blk_bytes = (int64_t)p.bs * d * 2;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-    // global sources.  X: thread -> 16-byte unit (tid & 7) of rows (tid >> 3) + 32 i
+    // ---- global sources.  A stage is 64 chunks of 1 KB: 32 of packed weights (straight
+    // copy), 32 of X (chunk c = rows 8c..8c+7, lane -> row 8c + lane/8, 16-byte unit
+    // lane%8 of the LDS row, which holds global unit (lane%8) ^ swz(row)).  Wave w copies
+    // chunks w, w+4, ...
     const char* xsrc[8];
-    const int xu = tid & 7, xr0 = tid >> 3;
+    {
+        const int pu = lane & 7, r0 = 8 * w + (lane >> 3);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        int tok = t0 + xr0 + 32 * i;
-        tok = tok < t1 ? tok : t1 - 1;          // rows past the range repeat the last token (masked later)
-        const int64_t blk = p.block_tables[(int64_t)r * 2 * p.max_blocks + (tok >> p.log2_bs)];
-        xsrc[i] = p.hidden_pages + blk * blk_bytes + ((int64_t)(tok & (p.bs - 1)) * d) * 2 + xu * 16;
+        for (int i = 0; i < 8; ++i) {
+            const int row = r0 + 32 * i;
+            int tok = t0 + row;
+            tok = tok < t1 ? tok : t1 - 1;      // rows past the range repeat the last token (masked later)
+            const int64_t blk = p.block_tables[(int64_t)r * 2 * p.max_blocks + (tok >> p.log2_bs)];
+            xsrc[i] = p.hidden_pages + blk * blk_bytes + ((int64_t)(tok & (p.bs - 1)) * d) * 2 + ((pu ^ swz(row)) * 16);
+        }
     }
-    const int xdst = xr0 * 128 + ((xu ^ swz(xr0)) * 16);          // + i * 32 rows * 128 B; swz(row + 32 i) = swz(row) ^ (4 i & 7)
-    const char* wsrc = p.W_packed + (int64_t)h * nkt * kTileBytes + tid * 16;
+    const char* wsrc = p.W_packed + (int64_t)h * nkt * kTileBytes + w * 1024 + lane * 16;
+    const uint32_t lds_w = lds_base + w * 1024;
+
+    // copies one half (i = i0..i0+3 of W and of X) of k-tile kt into stage `buf`
+    auto stage_half = [&](int kt, int buf, int i0) {
+#pragma unroll
+        for (int i = i0; i < i0 + 4; ++i)
+            gload_lds16(wsrc + (int64_t)kt * kTileBytes + i * 4096, lds_w + buf * kStageBytes + i * 4096);
+#pragma unroll
+        for (int i = i0; i < i0 + 4; ++i)
+            gload_lds16(xsrc[i] + kt * (kBK * 2), lds_w + buf * kStageBytes + kTileBytes + i * 4096);
+    };
+
+    // ---- LDS operand reads.  Row of fragment a: base row + 32 a; unit (2 ks + lane/32) ^ swz.
+    // swz(row + 32 a) = swz(row) ^ 4 (a & 1), so the lane part of the unit is one constant.
+    const int arow = mat * 128 + (lane & 31);
+    const int brow = th * 128 + (lane & 31);
+    const int a_c = ((lane >> 5) ^ swz(arow)) * 16;
+    const int b_c = ((lane >> 5) ^ swz(brow)) * 16;
+    const char* a_base = lds + arow * 128;
+    const char* b_base = lds + kTileBytes + brow * 128;
 
     f32x16_t acc[4][4];
 #pragma unroll
@@ -372,57 +405,69 @@ __device__ void hidden_item_mfma(const ItemParams& p, int r, int h, int t0, int 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-    uint4 xr[8], wr[8];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) wr[i] = *(const uint4*)(wsrc + (int64_t)kt * kTileBytes + i * 4096);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) xr[i] = *(const uint4*)(xsrc[i] + kt * (kBK * 2));
-    };
-    auto lstore = [&](int buf) {
-        char* wb = lds + buf * kStageBytes;
-        char* xb = wb + kTileBytes;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) *(uint4*)(wb + tid * 16 + i * 4096) = wr[i];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = xr0 + 32 * i;
-            *(uint4*)(xb + row * 128 + ((xu ^ swz(row)) * 16)) = xr[i];
-        }
-    };
-    (void)xdst;
-
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    const int arow = mat * 128 + (lane & 31);
-    const int brow = th * 128 + (lane & 31);
-    for (int kt = 0; kt < nkt; ++kt) {
-        if (kt + 1 < nkt) gload(kt + 1);
-        const char* wb = lds + (kt & 1) * kStageBytes;
-        const char* xb = wb + kTileBytes;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int kc = 2 * ks + (lane >> 5);
-            uint4 af[4], bf[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int row = arow + 32 * a;
-                af[a] = *(const uint4*)(wb + row * 128 + ((kc ^ swz(row)) * 16));
-            }
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int row = brow + 32 * b;
-                bf[b] = *(const uint4*)(xb + row * 128 + ((kc ^ swz(row)) * 16));
-            }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) acc[a][b] = mfma32<DT>(af[a], bf[b], acc[a][b]);
-        }
-        if (kt + 1 < nkt) lstore((kt + 1) & 1);
-        __syncthreads();
+    uint4 fa[2][4], fb[2][4];
+#define APT_LOAD_FRAGS(SET, BUF, KS)                                                                        \
+    _Pragma("unroll") for (int a_ = 0; a_ < 4; ++a_) {                                                      \
+        fa[SET][a_] = *(const uint4*)(a_base + (BUF) * kStageBytes + a_ * 4096 + (a_c ^ ((2 * (KS) * 16) ^ (64 * (a_ & 1))))); \
+        fb[SET][a_] = *(const uint4*)(b_base + (BUF) * kStageBytes + a_ * 4096 + (b_c ^ ((2 * (KS) * 16) ^ (64 * (a_ & 1))))); \
     }
+#define APT_MFMA_ROW(SET, A)                                                                                \
+    _Pragma("unroll") for (int b_ = 0; b_ < 4; ++b_) acc[A][b_] = mfma32<DT>(fa[SET][A], fb[SET][b_], acc[A][b_]);
+#define APT_MFMA_ALL(SET)                                                                                   \
+    _Pragma("unroll") for (int a_ = 0; a_ < 4; ++a_) { APT_MFMA_ROW(SET, a_) }
+
+    // one k-tile: sub-steps 0..2 read the next sub-step's operands while they multiply; before
+    // the last sub-step all waves meet (their parts of the next k-tile have landed, this
+    // k-tile's stage is no longer read), the stage is refilled with the k-tile after next and
+    // the next k-tile's first operands are read while the last sub-step multiplies.
+    // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
+#define APT_SCHED_STEP()                                                                                    \
+    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                  \
+    }                                                                                                       \
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#define APT_K_TILE(BUF)                                                                                     \
+    {                                                                                                       \
+        APT_LOAD_FRAGS(1, BUF, 1)                                                                           \
+        APT_MFMA_ALL(0)                                                                                     \
+        APT_SCHED_STEP()                                                                                    \
+        APT_LOAD_FRAGS(0, BUF, 2)                                                                           \
+        APT_MFMA_ALL(1)                                                                                     \
+        APT_SCHED_STEP()                                                                                    \
+        APT_LOAD_FRAGS(1, BUF, 3)                                                                           \
+        APT_MFMA_ALL(0)                                                                                     \
+        APT_SCHED_STEP()                                                                                    \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                    \
+        __syncthreads();                                                                                    \
+        if (kt + 1 < nkt) { APT_LOAD_FRAGS(0, (BUF) ^ 1, 0) }                                               \
+        if (kt + 2 < nkt) stage_half(kt + 2, BUF, 0);                                                       \
+        APT_MFMA_ROW(1, 0)                                                                                  \
+        APT_MFMA_ROW(1, 1)                                                                                  \
+        if (kt + 2 < nkt) stage_half(kt + 2, BUF, 4);                                                       \
+        APT_MFMA_ROW(1, 2)                                                                                  \
+        APT_MFMA_ROW(1, 3)                                                                                  \
+    }
+
+    stage_half(0, 0, 0);
+    stage_half(0, 0, 4);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    stage_half(1, 1, 0);
+    stage_half(1, 1, 4);
+    APT_LOAD_FRAGS(0, 0, 0)
+    for (int kt = 0; kt < nkt; kt += 2) {
+        APT_K_TILE(0)
+        ++kt;
+        APT_K_TILE(1)
+        --kt;
+    }
+#undef APT_K_TILE
+#undef APT_SCHED_STEP
+#undef APT_MFMA_ALL
+#undef APT_MFMA_ROW
+#undef APT_LOAD_FRAGS
+    __syncthreads();
 
     // ---- epilogue.  acc[a][b][e] of lane: channel 32a + 8(e/4) + 4(lane/32) + e%4 of the
     // wave's matrix, token th*128 + 32b + lane%32.

@@ -35,7 +35,7 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
     if ((s.block_size * lanes_per_row) % 64 != 0) return APT_ESHAPE;
     if (!(s.softmax_scale == s.softmax_scale)) return APT_EINVAL;
 
-    const bool mfma_ok = (s.dtype != APT_F32) && s.head_dim == 128 && (s.d_model % 64 == 0);
+    const bool mfma_ok = (s.dtype != APT_F32) && s.head_dim == 128 && (s.d_model % 128 == 0);
     if (s.hidden_impl == APT_HIDDEN_AUTO) s.hidden_impl = mfma_ok ? APT_HIDDEN_MFMA : APT_HIDDEN_VALU;
     if (s.hidden_impl == APT_HIDDEN_MFMA) {
         if (!mfma_ok) return APT_ESHAPE;

@@ -124,15 +124,20 @@ int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
  *   cache_kind_host uint8 [B], APT_KIND_KV or APT_KIND_HIDDEN
  *   plan_host       caller's buffer of plan_bytes bytes (see apt_plan_max_bytes); filled
  *                   with a self-contained blob of int32 words:
- *                     [0..15] header, [16..16+B) split_count, then ws_offset[B],
- *                     then (padded to a multiple of 4 words) items[n_items][4] =
- *                     (request, head, t0, t1)
+ *                     [0..15] header, [16..24] queue_offset, [32..32+B) split_count,
+ *                     then ws_offset[B], then (padded to a multiple of 4 words)
+ *                     items[n_items][4] = (request, head, t0, t1)
  *   info            optional, receives the counts and the workspace size
  * The rule: a request of n tokens is cut into ceil(n/C) ranges [s*C, min(n,(s+1)*C)),
  * C = hidden_chunk or kv_chunk by kind; ws_offset is the exclusive prefix sum of
  * split_count in request order; the partial result of (r, range s, head h) lives in
- * slot (ws_offset[r]+s)*n_heads + h; items are ordered hidden kind first, then by
- * request, range, head.  Integer-only; the same inputs always give the same bytes.
+ * slot (ws_offset[r]+s)*n_heads + h.  Items are ordered hidden kind first: 8 queues, queue x
+ * holding the heads with h % 8 == x (queue_offset[x] = its first item, queue_offset[8] = the
+ * number of hidden-kind items), in a queue first the full ranges by request, range, head, then
+ * the shorter last ranges by decreasing length (ties by request, head); then the KV kind by
+ * decreasing range length (ties by request, range, head).  The order only steers which
+ * workgroup takes which item (cache locality, balance); every item is independent.
+ * Integer-only; the same inputs always give the same bytes.
  * Errors: APT_EINVAL (null, B < 1, length < 1, unknown kind), APT_ERANGE (length
  * beyond max_blocks_per_req*block_size), APT_EWORKSPACE (plan_bytes too small),
  * APT_ESHAPE / APT_EDTYPE (bad shape).
@@ -210,6 +215,15 @@ int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, cons
  * calibrated against a kernel of known traffic (reads `bytes`, writes `bytes`).
  */
 int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
+
+/*
+ * Register-only fp16 MFMA loop (no memory traffic): n_workgroups workgroups of 256
+ * threads, each wave issuing iters * 16 independent 32x32x16 MFMAs
+ * (n_workgroups * 4 * iters * 16 * 32768 flops in total).  `out` (device) receives
+ * n_workgroups * 256 floats.  Exists to measure the rate the matrix pipes sustain on
+ * the device at hand, as context for the MFMA roofline fraction.
+ */
+int apt_probe_mfma(void* out, int n_workgroups, int iters, void* stream);
 
 #ifdef __cplusplus
 }

@@ -13,8 +13,15 @@ against it bit for bit:
   split_count over requests before r (request order);
 * the partial result of (request r, range s, head h) is stored in slot
   (ws_offset[r] + s) * H + h;
-* items are listed hidden-kind first, then KV-kind; within a kind by request,
-  then range, then head; an item is (r, h, t0, t1).
+* an item is (r, h, t0, t1).  Items are listed hidden-kind first, then KV-kind.
+* hidden-kind items are grouped into N_QUEUES = 8 queues, queue x holding the items
+  whose head h has h % 8 == x; the queues are concatenated in order x = 0..7 and
+  queue_offset[x] (9 entries) is the position of queue x's first item.  Inside a
+  queue: first the items whose range is a full hidden_chunk, ordered by request,
+  range, head; then the shorter (last) ranges, ordered by decreasing length, ties by
+  request, then head.
+* KV-kind items are ordered by decreasing length of their range, ties by request,
+  range, head.
 
 Block arithmetic of the cache map (Section 4.3): token j of a request lives in
 its (j // block_size)-th block at slot j % block_size; a request of n tokens owns
@@ -23,6 +30,7 @@ input hidden vector for the hidden kind).
 """
 KIND_KV = 0
 KIND_HIDDEN = 1
+N_QUEUES = 8
 
 
 def ceil_div(a, b):
@@ -43,25 +51,40 @@ def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk):
         split_count.append(ceil_div(n, c))
         ws_offset.append(run)
         run += split_count[-1]
-    items = []
-    n_hidden_items = 0
-    for kind in (KIND_HIDDEN, KIND_KV):
-        c = hidden_chunk if kind == KIND_HIDDEN else kv_chunk
+    def all_items(kind, c):
+        out = []
         for r in range(B):
             if int(cache_kind[r]) != kind:
                 continue
             n = int(ctx_lens[r])
             for s in range(split_count[r]):
                 for h in range(n_heads):
-                    items.append((r, h, s * c, min(n, (s + 1) * c)))
-        if kind == KIND_HIDDEN:
-            n_hidden_items = len(items)
+                    out.append((r, h, s * c, min(n, (s + 1) * c)))
+        return out
+
+    items = []
+    queue_offset = []
+    hidden = all_items(KIND_HIDDEN, hidden_chunk)
+    for x in range(N_QUEUES):
+        queue_offset.append(len(items))
+        mine = [it for it in hidden if it[1] % N_QUEUES == x]
+        full = [it for it in mine if it[3] - it[2] == hidden_chunk]
+        tails = [it for it in mine if it[3] - it[2] != hidden_chunk]
+        full.sort(key=lambda it: (it[0], it[2], it[1]))
+        tails.sort(key=lambda it: (-(it[3] - it[2]), it[0], it[1]))
+        items += full + tails
+    queue_offset.append(len(items))
+    n_hidden_items = len(items)
+    kv = all_items(KIND_KV, kv_chunk)
+    kv.sort(key=lambda it: (-(it[3] - it[2]), it[0], it[2], it[1]))
+    items += kv
     return {
         "split_count": split_count,
         "ws_offset": ws_offset,
         "items": items,
         "n_hidden_items": n_hidden_items,
         "n_partials": run,
+        "queue_offset": queue_offset,
     }
 
 

@@ -22,7 +22,7 @@ DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 
 EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt_plan_get_info", "apt_plan_upload",
            "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
-           "apt_hybrid_decode_attn_timed", "apt_copy_bytes"]
+           "apt_hybrid_decode_attn_timed", "apt_copy_bytes", "apt_probe_mfma"]
 
 
 class apt_shape(C.Structure):
@@ -161,14 +161,19 @@ def apt_copy_bytes(dst, src, nbytes, stream=0):
     _check(lib().apt_copy_bytes(_ptr(dst), _ptr(src), C.c_size_t(nbytes), C.c_void_p(stream)), "apt_copy_bytes")
 
 
+def apt_probe_mfma(out, n_workgroups, iters, stream=0):
+    _check(lib().apt_probe_mfma(_ptr(out), C.c_int(n_workgroups), C.c_int(iters), C.c_void_p(stream)), "apt_probe_mfma")
+
+
 # --- decoding of a plan blob for tests (layout documented in the header) ------------------
 def decode_plan(plan_host) -> dict:
     w = plan_host if isinstance(plan_host, np.ndarray) else plan_host.numpy()
     w = w.view(np.int32).reshape(-1)
     B, n_items, off = int(w[1]), int(w[3]), int(w[9])
     return {
-        "split_count": w[16:16 + B].tolist(),
-        "ws_offset": w[16 + B:16 + 2 * B].tolist(),
+        "split_count": w[32:32 + B].tolist(),
+        "ws_offset": w[32 + B:32 + 2 * B].tolist(),
+        "queue_offset": w[16:25].tolist(),
         "items": [tuple(int(v) for v in row) for row in w[off:off + 4 * n_items].reshape(n_items, 4)],
         "n_hidden_items": int(w[4]),
         "n_partials": int(w[5]),

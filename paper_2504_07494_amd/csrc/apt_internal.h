@@ -21,8 +21,10 @@ enum {
     APT_PW_HTOK_HI = 13,
     APT_PW_HEAD_DIM = 14,
     APT_PW_WORDS = 15,      // total words of the blob
-    APT_PW_HEADER = 16
+    APT_PW_QUEUE0 = 16,     // 9 words: start of each hidden-kind queue (in items), then the end
+    APT_PW_HEADER = 32
 };
+#define APT_N_QUEUES 8
 #define APT_PLAN_MAGIC 0x41505431
 
 // Tokens per work item.

@@ -12,6 +12,7 @@
 // Scores are kept in base-2 units: s2 = softmax_scale*log2(e)*<q,k>, weights 2^(s2 - m).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include "apt_internal.h"
 
 namespace {
@@ -40,6 +41,7 @@ struct ItemParams {
     int32_t B, H, d, bs, log2_bs, max_blocks;
     int32_t n_items, n_hidden_items, hidden_chunk, kv_chunk, items_off;
     float scale_log2e;
+    int32_t dbg;                  // experiment switches (0 in production)
 };
 
 // ---------------------------------------------------------------------------------
@@ -320,22 +322,42 @@ __device__ void hidden_item_valu(const ItemParams& p, int r, int h, int t0, int 
 }
 
 // ---------------------------------------------------------------------------------
-// hidden-kind item, MFMA version (fp16 / bf16, head_dim 128)
+// hidden-kind items, MFMA version (fp16 / bf16, head_dim 128): persistent workgroups
 // ---------------------------------------------------------------------------------
-// Per item: D[256 channels][256 tokens] = Wp_h[256][d] * X^T[d][256], channels 0..127 = K_h,
-// 128..255 = V_h.  Wave (mat, th) owns channels mat*128.. and tokens th*128.. as 4x4 tiles
-// of v_mfma_f32_32x32x16.  k runs in tiles of 64 through a double-buffered LDS stage:
-// per buffer 32 KB of packed weights (already in LDS order in memory) and 32 KB of X rows.
-// Rows are 128 B; the 16-byte unit c of a row sits at c ^ swz(row), which keeps both the
-// row-wise writes and the column-wise MFMA operand reads spread over all banks.
+// Per item: K_h and V_h of a tile of up to 256 tokens, [256 channels] x [256 tokens] with
+// k = d_model, on v_mfma_f32_32x32x16.  The four waves are (mat, th): mat 0 = K_h channels,
+// mat 1 = V_h channels; th picks the token blocks 2b + th (b = 0..3, 32 tokens each), so a
+// short tile leaves both halves the same number of blocks.  K waves multiply W (rows =
+// channels) by X^T and get D[channel][token]: a lane owns one token per tile column and
+// sums over channels in registers for the score.  V waves multiply X (rows = tokens) by
+// W^T and get D[token][channel]: a lane owns one channel and sums over tokens in registers
+// for the weighted value sum.  Both read the same LDS images; only which image feeds
+// which MFMA operand differs.
+//
+// k runs in tiles of 64 through two LDS stages, each 32 KB of packed weights (already in
+// LDS order in memory) and 32 KB of X rows, filled by global->LDS copies that bypass
+// registers.  Rows are 128 B; the 16-byte unit c of a row sits at c ^ swz(row), which
+// keeps the row-wise copies and the column-wise operand reads spread over all banks.
+//
+// A workgroup walks a queue of items (queue = blockIdx % 8, the XCD the workgroup is
+// expected to run on, so that the workgroups sharing an L2 work on few heads and few
+// token tiles at a time), then a share of the KV-kind items.  While one item's epilogue
+// runs, the first two k-tiles of the next item are already on their way into LDS.
 constexpr int kBK = 64;
 constexpr int kTileBytes = 256 * kBK * 2;              // 32 KB
 constexpr int kStageBytes = 2 * kTileBytes;            // W tile + X tile
-constexpr int kMfmaLds = 2 * kStageBytes;              // 128 KB
+constexpr int kMfmaScratch = 4096;                     // epilogue scratch behind the stages
+constexpr int kMfmaLds = 2 * kStageBytes + kMfmaScratch;
 
 __host__ __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
 
-template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
+// EXP: 0 = production.  Timing experiments (wrong results), bit mask: 1 = no MFMAs,
+// 2 = no staging copies inside the k loop
+template <int DT, int EXP = 0> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
+    if constexpr ((EXP & 1) != 0) {
+        c[0] += __uint_as_float(a.x ^ b.x);      // keeps the operand reads alive
+        return c;
+    }
     if constexpr (DT == 1)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8_t, a), __builtin_bit_cast(h8_t, b), c, 0, 0, 0);
     else
@@ -348,204 +370,316 @@ __device__ inline void gload_lds16(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
 }
 
-template <int DT>
-__device__ void hidden_item_mfma(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+template <int DT, int EXP>
+__global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
     constexpr int HD = 128;
-    const int tid = threadIdx.x, lane = tid & 63;
+    extern __shared__ __align__(16) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mat = w >> 1, th = w & 1;
     const int d = p.d;
     const int nkt = d / kBK;                 // even: d is a multiple of 128
     const int64_t blk_bytes = (int64_t)p.bs * d * 2;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t lds_w = lds_base + w * 1024;
+    const int4* items = (const int4*)(p.plan + p.items_off);
+    const int32_t* split_count = p.plan + APT_PW_HEADER;
+    const int32_t* ws_offset = split_count + p.B;
 
-    // ---- global sources.  A stage is 64 chunks of 1 KB: 32 of packed weights (straight
-    // copy), 32 of X (chunk c = rows 8c..8c+7, lane -> row 8c + lane/8, 16-byte unit
-    // lane%8 of the LDS row, which holds global unit (lane%8) ^ swz(row)).  Wave w copies
-    // chunks w, w+4, ...
-    const char* xsrc[8];
+    // epilogue scratch (not aliased with the stages)
+    float* scr = (float*)(lds + 4 * kTileBytes);
+    float* p_lds = scr;             // [256] softmax weights of the tile (per half, relative to its maximum)
+    float* qs_lds = scr + 256;      // [128] q * scale * log2(e)
+    float* bk_lds = scr + 384;      // [128]
+    float* bv_lds = scr + 512;      // [128]
+    float* o_lds = scr + 640;       // [2][128] per-half un-normalised output
+    float* ml_lds = scr + 896;      // [2][2] per-half (m, l); [4] = q . b_K
+
+    // ---- LDS layout: [W stage 0][W stage 1][X stage 0][X stage 1], 32 KB each, then scratch.
+    // Operand slot i of the "A" side is rows a_row + i * a_step, of the "B" side rows
+    // b_row + i * b_step, in the W image (K: A side, V: B side) or the X image.  Unit of
+    // sub-step ks: (2 ks + half) ^ swz(row), so its address is the ks = 0 address ^ (32 ks).
+    uint32_t a_addr[4], b_addr[4];
     {
-        const int pu = lane & 7, r0 = 8 * w + (lane >> 3);
+        const int wrow = mat * 128 + (lane & 31), xrow = th * 32 + (lane & 31);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = r0 + 32 * i;
-            int tok = t0 + row;
-            tok = tok < t1 ? tok : t1 - 1;      // rows past the range repeat the last token (masked later)
-            const int64_t blk = p.block_tables[(int64_t)r * 2 * p.max_blocks + (tok >> p.log2_bs)];
-            xsrc[i] = p.hidden_pages + blk * blk_bytes + ((int64_t)(tok & (p.bs - 1)) * d) * 2 + ((pu ^ swz(row)) * 16);
+        for (int i = 0; i < 4; ++i) {
+            const int wr = wrow + 32 * i, xr = xrow + 64 * i;
+            const uint32_t wa = wr * 128 + ((half ^ swz(wr)) * 16);
+            const uint32_t xa = 2 * kTileBytes + xr * 128 + ((half ^ swz(xr)) * 16);
+            a_addr[i] = mat == 0 ? wa : xa;
+            b_addr[i] = mat == 0 ? xa : wa;
         }
     }
-    const char* wsrc = p.W_packed + (int64_t)h * nkt * kTileBytes + w * 1024 + lane * 16;
-    const uint32_t lds_w = lds_base + w * 1024;
 
-    // copies one half (i = i0..i0+3 of W and of X) of k-tile kt into stage `buf`
-    auto stage_half = [&](int kt, int buf, int i0) {
+    // ---- this workgroup's share of the hidden-kind items
+    const int G = gridDim.x, g = blockIdx.x;
+    const int wpx = G >> 3;                                   // workgroups per queue (G is a multiple of 8)
+    const int q_end = p.plan[APT_PW_QUEUE0 + (g & 7) + 1];
+    int qi = p.plan[APT_PW_QUEUE0 + (g & 7)] + (g >> 3);
+
+    // per-lane state of an item: 8 X row sources (row 8 w + lane/8 + 32 i, unit (lane%8) ^ swz(row))
+    const int pu = lane & 7, r0 = 8 * w + (lane >> 3);
+    int4 it = make_int4(0, 0, 0, 1);
+    int32_t ids[8];
+    auto lookup = [&](const int4& item, int32_t* out) {       // block ids of this lane's 8 rows
 #pragma unroll
-        for (int i = i0; i < i0 + 4; ++i)
-            gload_lds16(wsrc + (int64_t)kt * kTileBytes + i * 4096, lds_w + buf * kStageBytes + i * 4096);
-#pragma unroll
-        for (int i = i0; i < i0 + 4; ++i)
-            gload_lds16(xsrc[i] + kt * (kBK * 2), lds_w + buf * kStageBytes + kTileBytes + i * 4096);
+        for (int i = 0; i < 8; ++i) {
+            int tok = item.z + r0 + 32 * i;
+            tok = tok < item.w ? tok : item.w - 1;            // rows past the range repeat the last token (masked later)
+            out[i] = p.block_tables[(int64_t)item.x * 2 * p.max_blocks + (tok >> p.log2_bs)];
+        }
+    };
+    const char* xsrc[8];
+    const char* wsrc = nullptr;
+#define APT_MAKE_SOURCES(XS, WS, ITEM, BLK)                                                                 \
+    {                                                                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                  \
+            const int row_ = r0 + 32 * i_;                                                                  \
+            int tok_ = (ITEM).z + row_;                                                                     \
+            tok_ = tok_ < (ITEM).w ? tok_ : (ITEM).w - 1;                                                   \
+            XS[i_] = p.hidden_pages + (int64_t)BLK[i_] * blk_bytes + ((int64_t)(tok_ & (p.bs - 1)) * d) * 2 + \
+                     ((pu ^ swz(row_)) * 16);                                                               \
+        }                                                                                                   \
+        WS = p.W_packed + (int64_t)(ITEM).y * nkt * kTileBytes + w * 1024 + lane * 16;                      \
+    }
+    // copies chunk j (0..7: weights, 8..15: X rows) of this wave's share of k-tile kt into stage `buf`
+    auto stage_chunk = [&](int kt, int buf, int j) {
+        if (p.dbg & 1) kt &= 1;      // experiment: re-read the first two k-tiles (cache-resident operands)
+        if (j < 8)
+            gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + buf * kTileBytes + j * 4096);
+        else
+            gload_lds16(xsrc[j - 8] + kt * (kBK * 2), lds_w + (2 + buf) * kTileBytes + (j - 8) * 4096);
     };
 
-    // ---- LDS operand reads.  Row of fragment a: base row + 32 a; unit (2 ks + lane/32) ^ swz.
-    // swz(row + 32 a) = swz(row) ^ 4 (a & 1), so the lane part of the unit is one constant.
-    const int arow = mat * 128 + (lane & 31);
-    const int brow = th * 128 + (lane & 31);
-    const int a_c = ((lane >> 5) ^ swz(arow)) * 16;
-    const int b_c = ((lane >> 5) ^ swz(brow)) * 16;
-    const char* a_base = lds + arow * 128;
-    const char* b_base = lds + kTileBytes + brow * 128;
+    bool have = qi < q_end;
+    if (have) {
+        it = items[qi];
+        lookup(it, ids);
+        APT_MAKE_SOURCES(xsrc, wsrc, it, ids)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) stage_chunk(0, 0, j);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) stage_chunk(1, 1, j);
+    }
 
     f32x16_t acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
-
     uint4 fa[2][4], fb[2][4];
 #define APT_LOAD_FRAGS(SET, BUF, KS)                                                                        \
-    _Pragma("unroll") for (int a_ = 0; a_ < 4; ++a_) {                                                      \
-        fa[SET][a_] = *(const uint4*)(a_base + (BUF) * kStageBytes + a_ * 4096 + (a_c ^ ((2 * (KS) * 16) ^ (64 * (a_ & 1))))); \
-        fb[SET][a_] = *(const uint4*)(b_base + (BUF) * kStageBytes + a_ * 4096 + (b_c ^ ((2 * (KS) * 16) ^ (64 * (a_ & 1))))); \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
+        fa[SET][i_] = *(const uint4*)(lds + (BUF) * kTileBytes + (a_addr[i_] ^ (32 * (KS))));               \
+        fb[SET][i_] = *(const uint4*)(lds + (BUF) * kTileBytes + (b_addr[i_] ^ (32 * (KS))));               \
     }
-#define APT_MFMA_ROW(SET, A)                                                                                \
-    _Pragma("unroll") for (int b_ = 0; b_ < 4; ++b_) acc[A][b_] = mfma32<DT>(fa[SET][A], fb[SET][b_], acc[A][b_]);
-#define APT_MFMA_ALL(SET)                                                                                   \
-    _Pragma("unroll") for (int a_ = 0; a_ < 4; ++a_) { APT_MFMA_ROW(SET, a_) }
-
+#define APT_MFMA_ALL(SET, FULL)                                                                             \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                  \
+            if (FULL || (i_ < ni && j_ < nj)) acc[i_][j_] = mfma32<DT, EXP>(fa[SET][i_], fb[SET][j_], acc[i_][j_]); \
+        }                                                                                                   \
+    }
+    // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
+#define APT_SCHED_STEP(FULL)                                                                                \
+    if (FULL) {                                                                                             \
+        _Pragma("unroll") for (int s_ = 0; s_ < 8; ++s_) {                                                  \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
+        }                                                                                                   \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                                  \
+    }
     // one k-tile: sub-steps 0..2 read the next sub-step's operands while they multiply; before
     // the last sub-step all waves meet (their parts of the next k-tile have landed, this
-    // k-tile's stage is no longer read), the stage is refilled with the k-tile after next and
-    // the next k-tile's first operands are read while the last sub-step multiplies.
-    // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
-#define APT_SCHED_STEP()                                                                                    \
-    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                  \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                  \
-    }                                                                                                       \
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-#define APT_K_TILE(BUF)                                                                                     \
+    // k-tile's stage is no longer read); then the next k-tile's first operands are read and,
+    // one copy per MFMA, the stage is refilled with the k-tile after next while the last
+    // sub-step multiplies.
+#define APT_K_TILE(BUF, STAGE, NEXT, FULL)                                                                  \
     {                                                                                                       \
         APT_LOAD_FRAGS(1, BUF, 1)                                                                           \
-        APT_MFMA_ALL(0)                                                                                     \
-        APT_SCHED_STEP()                                                                                    \
+        APT_MFMA_ALL(0, FULL)                                                                               \
+        APT_SCHED_STEP(FULL)                                                                                \
         APT_LOAD_FRAGS(0, BUF, 2)                                                                           \
-        APT_MFMA_ALL(1)                                                                                     \
-        APT_SCHED_STEP()                                                                                    \
+        APT_MFMA_ALL(1, FULL)                                                                               \
+        APT_SCHED_STEP(FULL)                                                                                \
         APT_LOAD_FRAGS(1, BUF, 3)                                                                           \
-        APT_MFMA_ALL(0)                                                                                     \
-        APT_SCHED_STEP()                                                                                    \
+        APT_MFMA_ALL(0, FULL)                                                                               \
+        APT_SCHED_STEP(FULL)                                                                                \
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                    \
         __syncthreads();                                                                                    \
-        if (kt + 1 < nkt) { APT_LOAD_FRAGS(0, (BUF) ^ 1, 0) }                                               \
-        if (kt + 2 < nkt) stage_half(kt + 2, BUF, 0);                                                       \
-        APT_MFMA_ROW(1, 0)                                                                                  \
-        APT_MFMA_ROW(1, 1)                                                                                  \
-        if (kt + 2 < nkt) stage_half(kt + 2, BUF, 4);                                                       \
-        APT_MFMA_ROW(1, 2)                                                                                  \
-        APT_MFMA_ROW(1, 3)                                                                                  \
+        if (NEXT) { APT_LOAD_FRAGS(0, (BUF) ^ 1, 0) }                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
+            _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                              \
+                if (STAGE && (EXP & 2) == 0) stage_chunk(kt + 2, BUF, i_ * 4 + j_);                         \
+                if (FULL || (i_ < ni && j_ < nj))                                                           \
+                    acc[i_][j_] = mfma32<DT, EXP>(fa[1][i_], fb[1][j_], acc[i_][j_]);                       \
+                __builtin_amdgcn_sched_barrier(0);                                                          \
+            }                                                                                               \
+        }                                                                                                   \
+    }
+#define APT_K_LOOP(FULL)                                                                                    \
+    {                                                                                                       \
+        int kt = 0;                                                                                         \
+        for (; kt + 2 < nkt; kt += 2) {                                                                     \
+            APT_K_TILE(0, true, true, FULL)                                                                 \
+            ++kt;                                                                                           \
+            APT_K_TILE(1, true, true, FULL)                                                                 \
+            --kt;                                                                                           \
+        }                                                                                                   \
+        APT_K_TILE(0, false, true, FULL)                                                                    \
+        APT_K_TILE(1, false, false, FULL)                                                                   \
     }
 
-    stage_half(0, 0, 0);
-    stage_half(0, 0, 4);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    stage_half(1, 1, 0);
-    stage_half(1, 1, 4);
-    APT_LOAD_FRAGS(0, 0, 0)
-    for (int kt = 0; kt < nkt; kt += 2) {
-        APT_K_TILE(0)
-        ++kt;
-        APT_K_TILE(1)
-        --kt;
+    while (have) {
+        const int r = it.x, h = it.y, t0 = it.z, nvalid = it.w - it.z;
+        // block ids of the next item: on their way while this item multiplies
+        const int nqi = qi + wpx;
+        const bool have_next = nqi < q_end;
+        int4 itn = it;
+        int32_t idsn[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) idsn[i] = 0;
+        if (have_next) {
+            itn = items[nqi];
+            lookup(itn, idsn);
+        }
+        // per-item constants of the epilogue
+        if (tid < HD) {
+            const float qv = load_elem<DT>(p.q, ((int64_t)r * p.H + h) * HD + tid) * p.scale_log2e;
+            const float bk = load_elem<DT>(p.b_K, (int64_t)h * HD + tid);
+            qs_lds[tid] = qv;
+            bk_lds[tid] = bk;
+            bv_lds[tid] = load_elem<DT>(p.b_V, (int64_t)h * HD + tid);
+            const float part = group_sum<64>(qv * bk);
+            if (lane == 0) ml_lds[4 + w] = part;      // waves 0 and 1: halves of q . b_K
+        }
+        // valid token blocks of this wave: blocks 2 b + th below ceil(nvalid / 32)
+        const int nvb = (nvalid + 31) >> 5;
+        const int nb = (nvb - th + 1) >> 1;
+        const int ni = mat == 0 ? 4 : nb, nj = mat == 0 ? nb : 4;
+
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                       // k-tiles 0 and 1 of this item are in LDS
+        // the next item's block ids have arrived; tell the compiler so, or the wait counts it
+        // would place inside the k loop for them would also wait for the staging copies
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(idsn[i]));
+        asm volatile("" ::"v"(itn.x), "v"(itn.y), "v"(itn.z), "v"(itn.w));
+        APT_LOAD_FRAGS(0, 0, 0)
+        if (nb == 4) APT_K_LOOP(true)
+        else APT_K_LOOP(false)
+
+        // both stages are free now (every wave has passed the last barrier of the k loop):
+        // start the next item's first two k-tiles, then finish this item
+        if (have_next) {
+            APT_MAKE_SOURCES(xsrc, wsrc, itn, idsn)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) stage_chunk(0, 0, j);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) stage_chunk(1, 1, j);
+        }
+
+        // ---- epilogue.  Register e of tile (i, j): row 8 (e/4) + 4 half + e%4 of the A-side
+        // block i, column lane%32 of the B-side block j.
+        if (mat == 0) {
+            // K wave: rows = channels 32 i + ..., columns = tokens of block 2 j + th
+            const float qb = ml_lds[4] + ml_lds[5];
+            float sp[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const float4 q4 = *(const float4*)(qs_lds + 32 * i + 8 * e4 + 4 * half);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        sp[j] = fmaf(acc[i][j][4 * e4 + 0], q4.x, sp[j]);
+                        sp[j] = fmaf(acc[i][j][4 * e4 + 1], q4.y, sp[j]);
+                        sp[j] = fmaf(acc[i][j][4 * e4 + 2], q4.z, sp[j]);
+                        sp[j] = fmaf(acc[i][j][4 * e4 + 3], q4.w, sp[j]);
+                    }
+                }
+            float m = kSentinel;
+            bool ok[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                sp[j] += __shfl_xor(sp[j], 32);
+                ok[j] = (2 * j + th) * 32 + (lane & 31) < nvalid;
+                sp[j] = ok[j] ? sp[j] + qb : kSentinel;
+                m = fmaxf(m, sp[j]);
+            }
+            m = group_max<32>(m);
+            float l = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float pw = ok[j] ? fast_exp2(sp[j] - m) : 0.f;
+                l += pw;
+                if (lane < 32) p_lds[(2 * j + th) * 32 + lane] = pw;
+            }
+            l = group_sum<32>(l);
+            if (lane == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
+        }
+        __syncthreads();
+        if (mat == 1) {
+            // V wave: rows = tokens of block 2 i + th, columns = channels 32 j + lane%32
+            float o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const float4 p4 = *(const float4*)(p_lds + (2 * i + th) * 32 + 8 * e4 + 4 * half);
+                    if (i < ni) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            o[j] = fmaf(acc[i][j][4 * e4 + 0], p4.x, o[j]);
+                            o[j] = fmaf(acc[i][j][4 * e4 + 1], p4.y, o[j]);
+                            o[j] = fmaf(acc[i][j][4 * e4 + 2], p4.z, o[j]);
+                            o[j] = fmaf(acc[i][j][4 * e4 + 3], p4.w, o[j]);
+                        }
+                    }
+                }
+            const float l = ml_lds[th * 2 + 1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[j] += __shfl_xor(o[j], 32);
+                if (lane < 32) o_lds[th * 128 + 32 * j + lane] = fmaf(l, bv_lds[32 * j + lane], o[j]);
+            }
+        }
+        __syncthreads();
+        if (tid < HD) {
+            const float m0 = ml_lds[0], l0 = ml_lds[1], m1 = ml_lds[2], l1 = ml_lds[3];
+            const float M = fmaxf(m0, m1);
+            const float w0 = fast_exp2(m0 - M), w1 = fast_exp2(m1 - M);
+            const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.hidden_chunk) * p.H + h;
+            p.ws_acc[slot * HD + tid] = o_lds[tid] * w0 + o_lds[128 + tid] * w1;
+            if (tid == 0) p.ws_ml[slot] = make_float2(M, l0 * w0 + l1 * w1);
+        }
+        have = have_next;
+        qi = nqi;
+        it = itn;
     }
+#undef APT_K_LOOP
+#undef APT_MAKE_SOURCES
 #undef APT_K_TILE
 #undef APT_SCHED_STEP
 #undef APT_MFMA_ALL
-#undef APT_MFMA_ROW
 #undef APT_LOAD_FRAGS
-    __syncthreads();
 
-    // ---- epilogue.  acc[a][b][e] of lane: channel 32a + 8(e/4) + 4(lane/32) + e%4 of the
-    // wave's matrix, token th*128 + 32b + lane%32.
-    float* s_lds = (float*)lds;            // [256] scores
-    float* o_lds = s_lds + 256;            // [2][128] per-half un-normalised output
-    float* ml_lds = o_lds + 256;           // [2][2]
-    const int half = lane >> 5;
-    if (mat == 0) {
-        float qv[4][16];
-        float qb = 0.f;
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int ch = 32 * a + 8 * (e >> 2) + 4 * half + (e & 3);
-                qv[a][e] = load_elem<DT>(p.q, ((int64_t)r * p.H + h) * HD + ch) * p.scale_log2e;
-                qb = fmaf(qv[a][e], load_elem<DT>(p.b_K, (int64_t)h * HD + ch), qb);
-            }
-        qb += __shfl_xor(qb, 32);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            float sp = 0.f;
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sp = fmaf(acc[a][b][e], qv[a][e], sp);
-            sp += __shfl_xor(sp, 32);
-            if (lane < 32) s_lds[th * 128 + 32 * b + lane] = sp + qb;
-        }
-    }
+    // ---- then a share of the KV-kind items, longest first
     __syncthreads();
-    if (mat == 1) {
-        const int nvalid = t1 - t0;
-        float s[4], pw[4];
-        float m = kSentinel;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int tl = th * 128 + 32 * b + (lane & 31);
-            s[b] = tl < nvalid ? s_lds[tl] : kSentinel;
-            m = fmaxf(m, s[b]);
-        }
-        m = group_max<32>(m);
-        float l = 0.f;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int tl = th * 128 + 32 * b + (lane & 31);
-            pw[b] = tl < nvalid ? fast_exp2(s[b] - m) : 0.f;
-            l += pw[b];
-        }
-        l = group_sum<32>(l);
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float o = 0.f;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) o = fmaf(pw[b], acc[a][b][e], o);
-                o = group_sum<32>(o);
-                const int ch = 32 * a + 8 * (e >> 2) + 4 * half + (e & 3);
-                if ((lane & 31) == 0) o_lds[th * 128 + ch] = fmaf(l, load_elem<DT>(p.b_V, (int64_t)h * HD + ch), o);
-            }
-        if (lane == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
-    }
-    __syncthreads();
-    if (tid < HD) {
-        const float m0 = ml_lds[0], l0 = ml_lds[1], m1 = ml_lds[2], l1 = ml_lds[3];
-        const float M = fmaxf(m0, m1);
-        const float w0 = fast_exp2(m0 - M), w1 = fast_exp2(m1 - M);
-        const int32_t* split_count = p.plan + APT_PW_HEADER;
-        const int32_t* ws_offset = split_count + p.B;
-        const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.hidden_chunk) * p.H + h;
-        p.ws_acc[slot * HD + tid] = o_lds[tid] * w0 + o_lds[128 + tid] * w1;
-        if (tid == 0) p.ws_ml[slot] = make_float2(M, l0 * w0 + l1 * w1);
+    for (int i = p.n_hidden_items + g; i < p.n_items; i += G) {
+        const int4 kv = items[i];
+        kv_item<DT, HD>(p, kv.x, kv.y, kv.z, kv.w, lds);
+        __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------------------------
-// the items kernel.  HIMPL: 0 = no hidden-kind items in the plan, 1 = plain ALU, 2 = MFMA
+// the items kernel, one workgroup per item.  HIMPL: 0 = no hidden-kind items in the plan,
+// 1 = plain-ALU hidden kernel.  (Plans with MFMA hidden items run apt_items_mfma_kernel.)
 // ---------------------------------------------------------------------------------
 template <int DT, int HD, int HIMPL>
 __global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
@@ -555,7 +689,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
     const int4 it = ((const int4*)(p.plan + p.items_off))[item];
     if (item < p.n_hidden_items) {
         if constexpr (HIMPL == 1) hidden_item_valu<DT, HD>(p, it.x, it.y, it.z, it.w, lds);
-        if constexpr (HIMPL == 2) hidden_item_mfma<DT>(p, it.x, it.y, it.z, it.w, lds);
     } else {
         kv_item<DT, HD>(p, it.x, it.y, it.z, it.w, lds);
     }
@@ -627,6 +760,28 @@ __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const ui
     for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// Register-only MFMA loop: 4 waves per workgroup, 16 independent 32x32x16 fp16 MFMAs per
+// iteration and wave, no memory traffic.  Measures the rate the matrix pipes sustain.
+__global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, int iters) {
+    f32x16_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    uint4 a = make_uint4(threadIdx.x, 0x3c003c00u, 0x3c003c00u, blockIdx.x);
+    uint4 b = make_uint4(0x3c003c00u, threadIdx.x, 0x38003800u, 0x3c003c00u);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = mfma32<1>(a, b, acc[i]);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sum += acc[i][e];
+    out[(int64_t)blockIdx.x * kThreads + threadIdx.x] = sum;
+}
+
 // ---------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------
@@ -643,6 +798,23 @@ int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
+// persistent launch: one workgroup per compute unit, a multiple of 8
+template <int DT, int EXP>
+int launch_mfma(const ItemParams& p, hipStream_t st) {
+    auto kern = apt_items_mfma_kernel<DT, EXP>;
+    static int n_wg = 0;
+    if (n_wg == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return APT_EHIP;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return APT_EHIP;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return APT_EHIP;
+        n_wg = cus >= 8 ? (cus / 8) * 8 : 8;
+    }
+    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), kMfmaLds, st, p);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
 template <int DT, int HD>
 int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
     constexpr int EB = Elt<DT>::bytes;
@@ -655,7 +827,11 @@ int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
         return launch_items<DT, HD, 1>(p, v > kv_lds ? v : kv_lds, st);
     }
     if constexpr (DT != 0 && HD == 128) {
-        return launch_items<DT, HD, 2>(p, kMfmaLds, st);
+        if constexpr (DT == 1) {     // timing experiments (wrong results), fp16 only
+            if ((p.dbg >> 4) == 1) return launch_mfma<DT, 1>(p, st);
+            if ((p.dbg >> 4) == 2) return launch_mfma<DT, 2>(p, st);
+        }
+        return launch_mfma<DT, 0>(p, st);
     }
     return APT_ESHAPE;
 }
@@ -702,6 +878,12 @@ extern "C" int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* st
     if (blocks > 256 * 64) blocks = 256 * 64;
     hipLaunchKernelGGL(apt_copy_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
                        (uint4*)dst, (const uint4*)src, n);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, void* stream) {
+    if (!out || n_workgroups < 1 || iters < 1) return APT_EINVAL;
+    hipLaunchKernelGGL(apt_mfma_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, (hipStream_t)stream, (float*)out, iters);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
@@ -755,6 +937,10 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     p.n_items = n_items; p.n_hidden_items = n_hidden;
     p.hidden_chunk = rs.s.hidden_chunk; p.kv_chunk = rs.s.kv_chunk; p.items_off = pw[APT_PW_ITEMS_OFF];
     p.scale_log2e = rs.s.softmax_scale * 1.4426950408889634f;
+    {
+        static const int dbg = getenv("APT_DEBUG") ? atoi(getenv("APT_DEBUG")) : 0;
+        p.dbg = dbg;
+    }
     hipStream_t st = (hipStream_t)stream;
 
     const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;

@@ -1,6 +1,8 @@
 // Host side of the library: status strings, shape checks, the ragged work
 // partitioner and the cache-map range check.  No device code here.
 #include <string.h>
+#include <algorithm>
+#include <vector>
 #include "apt_internal.h"
 
 extern "C" const char* apt_strerror(int status) {
@@ -133,24 +135,41 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
         ws_offset[r] = run;
         run += split_count[r];
     }
-    // pass 2: items, hidden kind first
+    // pass 2: items.  Hidden kind first, in APT_N_QUEUES queues by head % 8; in a queue the
+    // full ranges come first (request, range, head order), then the last, shorter ranges by
+    // decreasing length.  Then the KV kind by decreasing range length.
     int32_t* it = w + items_off;
-    for (int pass = 0; pass < 2; ++pass) {
-        const uint8_t want = pass == 0 ? APT_KIND_HIDDEN : APT_KIND_KV;
-        const int c = pass == 0 ? rs.s.hidden_chunk : rs.s.kv_chunk;
-        for (int r = 0; r < B; ++r) {
+    int32_t* const it0 = it;
+    std::vector<int32_t> tails;     // requests with a shorter last range, to be ordered by its length
+    auto emit_kind = [&](uint8_t want, int c, int h_first, int h_step) {
+        for (int r = 0; r < B; ++r) {       // full ranges
             if (cache_kind[r] != want) continue;
-            const int n = ctx_lens[r];
-            for (int sp = 0; sp < split_count[r]; ++sp) {
-                const int t0 = sp * c;
-                const int t1 = t0 + c < n ? t0 + c : n;
-                for (int h = 0; h < H; ++h) {
-                    it[0] = r; it[1] = h; it[2] = t0; it[3] = t1;
+            const int nfull = ctx_lens[r] / c;
+            for (int sp = 0; sp < nfull; ++sp)
+                for (int h = h_first; h < H; h += h_step) {
+                    it[0] = r; it[1] = h; it[2] = sp * c; it[3] = sp * c + c;
                     it += 4;
                 }
+        }
+        tails.clear();
+        for (int r = 0; r < B; ++r)
+            if (cache_kind[r] == want && ctx_lens[r] % c != 0) tails.push_back(r);
+        std::stable_sort(tails.begin(), tails.end(),
+                         [&](int32_t a, int32_t b) { return ctx_lens[a] % c > ctx_lens[b] % c; });
+        for (int32_t r : tails) {
+            const int t0 = (ctx_lens[r] / c) * c;
+            for (int h = h_first; h < H; h += h_step) {
+                it[0] = r; it[1] = h; it[2] = t0; it[3] = ctx_lens[r];
+                it += 4;
             }
         }
+    };
+    for (int x = 0; x < APT_N_QUEUES; ++x) {
+        w[APT_PW_QUEUE0 + x] = (int32_t)((it - it0) / 4);
+        emit_kind(APT_KIND_HIDDEN, rs.s.hidden_chunk, x, APT_N_QUEUES);
     }
+    w[APT_PW_QUEUE0 + APT_N_QUEUES] = (int32_t)((it - it0) / 4);
+    emit_kind(APT_KIND_KV, rs.s.kv_chunk, 0, 1);
     if (info) return apt_plan_get_info(plan_host, info);
     return APT_OK;
 }

@@ -22,6 +22,9 @@ def test_every_token_is_covered_exactly_once(seed, B, hi, H, ch, ck):
         c = ch if kinds[r] == po.KIND_HIDDEN else ck
         assert t1 - t0 <= c and t0 % c == 0
         assert (i < p["n_hidden_items"]) == (kinds[r] == po.KIND_HIDDEN)
+        if i < p["n_hidden_items"]:
+            x = h % po.N_QUEUES
+            assert p["queue_offset"][x] <= i < p["queue_offset"][x + 1]
         cover[r][h, t0:t1] += 1
         slot = po.partial_slot(p["ws_offset"], H, r, t0 // c, h)
         assert slot not in slots
@@ -36,6 +39,12 @@ def test_every_token_is_covered_exactly_once(seed, B, hi, H, ch, ck):
         c = ch if kinds[r] == po.KIND_HIDDEN else ck
         assert p["split_count"][r] == (int(lens[r]) + c - 1) // c
     assert len(p["items"]) == sum(H * s for s in p["split_count"])
+    assert p["queue_offset"][0] == 0 and p["queue_offset"][-1] == p["n_hidden_items"]
+    assert all(a <= b for a, b in zip(p["queue_offset"][:-1], p["queue_offset"][1:]))
+    # inside a queue and inside the KV part the cost (range length) never increases
+    for lo, hi in list(zip(p["queue_offset"][:-1], p["queue_offset"][1:])) + [(p["n_hidden_items"], len(p["items"]))]:
+        lens_ = [t1 - t0 for (_, _, t0, t1) in p["items"][lo:hi]]
+        assert lens_ == sorted(lens_, reverse=True)
 
 
 def test_item_order_hand_example():
@@ -44,11 +53,14 @@ def test_item_order_hand_example():
     assert p["split_count"] == [2, 3, 1]
     assert p["ws_offset"] == [0, 2, 5]
     assert p["n_hidden_items"] == 6
+    # queue 0 = head 0 (full ranges, then the 1-token tail), queue 1 = head 1, queues 2..7 empty;
+    # KV items by decreasing length: 4, 4, 3, 3, 1, 1
     assert p["items"] == [
-        (1, 0, 0, 4), (1, 1, 0, 4), (1, 0, 4, 8), (1, 1, 4, 8), (1, 0, 8, 9), (1, 1, 8, 9),
-        (0, 0, 0, 4), (0, 1, 0, 4), (0, 0, 4, 5), (0, 1, 4, 5),
-        (2, 0, 0, 3), (2, 1, 0, 3),
+        (1, 0, 0, 4), (1, 0, 4, 8), (1, 0, 8, 9),
+        (1, 1, 0, 4), (1, 1, 4, 8), (1, 1, 8, 9),
+        (0, 0, 0, 4), (0, 1, 0, 4), (2, 0, 0, 3), (2, 1, 0, 3), (0, 0, 4, 5), (0, 1, 4, 5),
     ]
+    assert p["queue_offset"] == [0, 3, 6, 6, 6, 6, 6, 6, 6]
 
 
 def test_plan_rejects_bad_input():

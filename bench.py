@@ -81,6 +81,10 @@ def main():
     ap.add_argument("--kv-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pairs-per-thread", type=int, default=8)
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time hidden-cache ratios 0/25/50/75/100 %% of the same config (adds a 'sweep' list)")
+    ap.add_argument("--probe", choices=["copy", "mfma"], default=None,
+                    help="run only a calibration kernel (plain copy of 1 GiB, or the register-only MFMA loop)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -89,6 +93,9 @@ def main():
     import torch
     from paper_2504_07494_amd import workloads as wl
     from paper_2504_07494_amd.harness import DecodeRunner
+
+    if args.probe:
+        return run_probe(args)
 
     cfg = wl.CONFIGS[args.config]
     if args.hidden_ratio is not None:
@@ -141,7 +148,8 @@ def main():
         ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey)}
-    roof.update({"kernel": "apt_items_kernel", "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
+    mfma_items = rn.info.n_hidden_items > 0 and rn.info.hidden_impl == 2
+    roof.update({"kernel": "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel", "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
                  "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
 
     result = {
@@ -181,7 +189,80 @@ def main():
         }
         result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
                                    "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
+    if args.sweep:
+        result["sweep"] = [time_ratio(cfg, r, args) for r in (0.0, 0.25, 0.5, 0.75, 1.0)]
     print(json.dumps(result))
+
+
+def time_ratio(cfg, ratio, args):
+    """Item-kernel time and roofline fractions of one hidden-cache ratio (same lengths, nested kind sets)."""
+    import numpy as np
+    import torch
+    from paper_2504_07494_amd import workloads as wl
+    from paper_2504_07494_amd.harness import DecodeRunner
+    c = wl.with_ratio(cfg, ratio)
+    batch = wl.make_batch(c)
+    layer = wl.make_layer(batch, workers=min(16, os.cpu_count() or 8))
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk)
+    dl = rn.upload(layer)
+    for _ in range(args.warmup):
+        rn.plan()
+        rn.run(dl)
+    torch.cuda.synchronize()
+    ev = HipEvents(args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        rn.plan()
+        rn.run(dl, ev.pairs[i][0], ev.pairs[i][1])
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kms = float(np.mean([ev.elapsed_ms(i) for i in range(args.steps)]))
+    ev.close()
+    d, e = c.d_model, wl.ELEM_BYTES[c.dtype]
+    flops = 4.0 * d * d * batch.hidden_tokens
+    nbytes = 2.0 * d * e * batch.kv_tokens + 1.0 * d * e * batch.hidden_tokens
+    del rn, dl, layer
+    torch.cuda.empty_cache()
+    return {"hidden_ratio": ratio, "total_tokens": batch.total_tokens, "hidden_tokens": batch.hidden_tokens,
+            "ms_per_step": ms_step, "kernel_ms": kms, "cached_tokens_per_s": batch.total_tokens / (ms_step * 1e-3),
+            "mfma_tflops": flops / (kms * 1e-3) / 1e12, "mfma_frac": flops / (kms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS[c.dtype],
+            "hbm_gbs": nbytes / (kms * 1e-3) / 1e9, "hbm_frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+
+def run_probe(args):
+    """Calibration kernels of known work, for counter scaling and as context for the peaks."""
+    import torch
+    from paper_2504_07494_amd import binding as ab
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream(dev).cuda_stream
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.probe == "copy":
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup):
+            ab.apt_copy_bytes(dst, src, n, st)
+        a.record()
+        for _ in range(args.steps):
+            ab.apt_copy_bytes(dst, src, n, st)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        print(json.dumps({"probe": "copy", "bytes_read": n, "bytes_written": n, "ms": ms,
+                          "read_plus_write_GBs": 2 * n / ms / 1e6}))
+    else:
+        nwg, iters = 1024, 5000
+        out = torch.empty(nwg * 256, dtype=torch.float32, device=dev)
+        for _ in range(args.warmup):
+            ab.apt_probe_mfma(out, nwg, iters, st)
+        a.record()
+        for _ in range(args.steps):
+            ab.apt_probe_mfma(out, nwg, iters, st)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / args.steps
+        print(json.dumps({"probe": "mfma", "flops": nwg * 4 * iters * 16 * 32768.0, "ms": ms,
+                          "TFLOPs": nwg * 4 * iters * 16 * 32768.0 / ms / 1e9}))
 
 
 if __name__ == "__main__":

@@ -23,7 +23,7 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
-        sys.stderr.write(out + "\n")
+        sys.stderr.write("\n".join(l for l in out.splitlines() if "error" in l) [:4000] + "\n")
         raise RuntimeError("hipcc failed")
     if verbose:
         print(out)

@@ -42,6 +42,7 @@ struct ItemParams {
     int32_t n_items, n_hidden_items, hidden_chunk, kv_chunk, items_off;
     float scale_log2e;
     int32_t dbg;                  // experiment switches (0 in production)
+    long long* dbg_buf;           // experiment output: per-workgroup clock stamps (null in production)
 };
 
 // ---------------------------------------------------------------------------------
@@ -334,22 +335,25 @@ __device__ void hidden_item_valu(const ItemParams& p, int r, int h, int t0, int 
 // for the weighted value sum.  Both read the same LDS images; only which image feeds
 // which MFMA operand differs.
 //
-// k runs in tiles of 64 through two LDS stages, each 32 KB of packed weights (already in
-// LDS order in memory) and 32 KB of X rows, filled by global->LDS copies that bypass
-// registers.  Rows are 128 B; the 16-byte unit c of a row sits at c ^ swz(row), which
-// keeps the row-wise copies and the column-wise operand reads spread over all banks.
+// k runs in tiles of 32 through four LDS stages, each 16 KB of packed weights (already in
+// LDS order in memory) and 16 KB of X rows, filled by global->LDS copies that bypass
+// registers; up to four k-tiles are in flight or waiting while one is multiplied.  Rows are 64 B; the
+// 16-byte unit c of a row sits at c ^ swz(row), which keeps the row-wise copies and the
+// column-wise operand reads spread over all banks.
 //
-// A workgroup walks a queue of items (queue = blockIdx % 8, the XCD the workgroup is
-// expected to run on, so that the workgroups sharing an L2 work on few heads and few
-// token tiles at a time), then a share of the KV-kind items.  While one item's epilogue
-// runs, the first two k-tiles of the next item are already on their way into LDS.
-constexpr int kBK = 64;
-constexpr int kTileBytes = 256 * kBK * 2;              // 32 KB
-constexpr int kStageBytes = 2 * kTileBytes;            // W tile + X tile
+// A workgroup walks a queue of items (queue = blockIdx % 8, the XCD the workgroup runs
+// on, so that the workgroups sharing an L2 work on few heads and few token tiles at a
+// time), then a share of the KV-kind items.  While one item's epilogue runs, the first
+// k-tiles of the next item are already on their way into LDS.
+constexpr int kBK = 32;
+constexpr int kRowBytes = kBK * 2;                     // 64 B
+constexpr int kTileBytes = 256 * kRowBytes;            // 16 KB
+constexpr int kStages = 4;
 constexpr int kMfmaScratch = 4096;                     // epilogue scratch behind the stages
-constexpr int kMfmaLds = 2 * kStageBytes + kMfmaScratch;
+constexpr int kMfmaLds = 2 * kStages * kTileBytes + kMfmaScratch;
+constexpr int kStageLoads = 8;                         // copies per wave and k-tile: 4 of W, 4 of X
 
-__host__ __device__ inline int swz(int row) { return (row ^ (row >> 3)) & 7; }
+__host__ __device__ inline int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
 
 // EXP: 0 = production.  Timing experiments (wrong results), bit mask: 1 = no MFMAs,
 // 2 = no staging copies inside the k loop
@@ -369,6 +373,14 @@ template <int DT, int EXP = 0> __device__ inline f32x16_t mfma32(const uint4& a,
 __device__ inline void gload_lds16(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
 }
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4_t lds_u32x4_t;
+// 16-byte LDS read at an absolute LDS address (the dynamic LDS base is folded into the operand addresses once)
+__device__ inline uint4 lds_read16(uint32_t addr) {
+    const u32x4_t v = *(const lds_u32x4_t*)(uintptr_t)addr;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 template <int DT, int EXP>
 __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
@@ -378,7 +390,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mat = w >> 1, th = w & 1;
     const int d = p.d;
-    const int nkt = d / kBK;                 // even: d is a multiple of 128
+    const int nkt = d / kBK;                 // a multiple of 4: d is a multiple of 128
     const int64_t blk_bytes = (int64_t)p.bs * d * 2;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const uint32_t lds_w = lds_base + w * 1024;
@@ -386,27 +398,27 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     const int32_t* split_count = p.plan + APT_PW_HEADER;
     const int32_t* ws_offset = split_count + p.B;
 
-    // epilogue scratch (not aliased with the stages)
-    float* scr = (float*)(lds + 4 * kTileBytes);
+    // ---- LDS layout: W stages 0..3 (16 KB each), X stages 0..3, then the epilogue scratch
+    float* scr = (float*)(lds + 2 * kStages * kTileBytes);
     float* p_lds = scr;             // [256] softmax weights of the tile (per half, relative to its maximum)
     float* qs_lds = scr + 256;      // [128] q * scale * log2(e)
     float* bk_lds = scr + 384;      // [128]
     float* bv_lds = scr + 512;      // [128]
     float* o_lds = scr + 640;       // [2][128] per-half un-normalised output
-    float* ml_lds = scr + 896;      // [2][2] per-half (m, l); [4] = q . b_K
+    float* ml_lds = scr + 896;      // [2][2] per-half (m, l); [4], [5] = halves of q . b_K
 
-    // ---- LDS layout: [W stage 0][W stage 1][X stage 0][X stage 1], 32 KB each, then scratch.
     // Operand slot i of the "A" side is rows a_row + i * a_step, of the "B" side rows
     // b_row + i * b_step, in the W image (K: A side, V: B side) or the X image.  Unit of
-    // sub-step ks: (2 ks + half) ^ swz(row), so its address is the ks = 0 address ^ (32 ks).
+    // sub-step ks: (2 ks + half) ^ swz(row), so its address is the ks = 0 address ^ (32 ks);
+    // swz does not change with the slot (row steps of 32 and 64).
     uint32_t a_addr[4], b_addr[4];
     {
         const int wrow = mat * 128 + (lane & 31), xrow = th * 32 + (lane & 31);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int wr = wrow + 32 * i, xr = xrow + 64 * i;
-            const uint32_t wa = wr * 128 + ((half ^ swz(wr)) * 16);
-            const uint32_t xa = 2 * kTileBytes + xr * 128 + ((half ^ swz(xr)) * 16);
+            const uint32_t wa = lds_base + wr * kRowBytes + ((half ^ swz(wr)) * 16);
+            const uint32_t xa = lds_base + kStages * kTileBytes + xr * kRowBytes + ((half ^ swz(xr)) * 16);
             a_addr[i] = mat == 0 ? wa : xa;
             b_addr[i] = mat == 0 ? xa : wa;
         }
@@ -418,24 +430,25 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     const int q_end = p.plan[APT_PW_QUEUE0 + (g & 7) + 1];
     int qi = p.plan[APT_PW_QUEUE0 + (g & 7)] + (g >> 3);
 
-    // per-lane state of an item: 8 X row sources (row 8 w + lane/8 + 32 i, unit (lane%8) ^ swz(row))
-    const int pu = lane & 7, r0 = 8 * w + (lane >> 3);
+    // per-lane state of an item: 4 X row sources.  An X chunk of 1 KB is 16 rows; wave w
+    // copies chunks w + 4 i: row 16 w + lane/4 + 64 i, LDS unit lane%4 = global unit (lane%4) ^ swz(row)
+    const int pu = lane & 3, r0 = 16 * w + (lane >> 2);
     int4 it = make_int4(0, 0, 0, 1);
-    int32_t ids[8];
-    auto lookup = [&](const int4& item, int32_t* out) {       // block ids of this lane's 8 rows
+    int32_t ids[4];
+    auto lookup = [&](const int4& item, int32_t* out) {       // block ids of this lane's 4 rows
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int tok = item.z + r0 + 32 * i;
+        for (int i = 0; i < 4; ++i) {
+            int tok = item.z + r0 + 64 * i;
             tok = tok < item.w ? tok : item.w - 1;            // rows past the range repeat the last token (masked later)
             out[i] = p.block_tables[(int64_t)item.x * 2 * p.max_blocks + (tok >> p.log2_bs)];
         }
     };
-    const char* xsrc[8];
+    const char* xsrc[4];
     const char* wsrc = nullptr;
 #define APT_MAKE_SOURCES(XS, WS, ITEM, BLK)                                                                 \
     {                                                                                                       \
-        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                                                  \
-            const int row_ = r0 + 32 * i_;                                                                  \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
+            const int row_ = r0 + 64 * i_;                                                                  \
             int tok_ = (ITEM).z + row_;                                                                     \
             tok_ = tok_ < (ITEM).w ? tok_ : (ITEM).w - 1;                                                   \
             XS[i_] = p.hidden_pages + (int64_t)BLK[i_] * blk_bytes + ((int64_t)(tok_ & (p.bs - 1)) * d) * 2 + \
@@ -443,99 +456,108 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         }                                                                                                   \
         WS = p.W_packed + (int64_t)(ITEM).y * nkt * kTileBytes + w * 1024 + lane * 16;                      \
     }
-    // copies chunk j (0..7: weights, 8..15: X rows) of this wave's share of k-tile kt into stage `buf`
-    auto stage_chunk = [&](int kt, int buf, int j) {
-        if (p.dbg & 1) kt &= 1;      // experiment: re-read the first two k-tiles (cache-resident operands)
-        if (j < 8)
-            gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + buf * kTileBytes + j * 4096);
+    // copies chunk j (0..3: weights, 4..7: X rows) of this wave's share of k-tile kt into stage st
+    auto stage_chunk = [&](int kt, int st, int j) {
+        if (p.dbg & 1) kt &= 3;      // experiment: re-read the first four k-tiles (cache-resident operands)
+        if (j < 4)
+            gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + st * kTileBytes + j * 4096);
         else
-            gload_lds16(xsrc[j - 8] + kt * (kBK * 2), lds_w + (2 + buf) * kTileBytes + (j - 8) * 4096);
+            gload_lds16(xsrc[j - 4] + kt * kRowBytes, lds_w + (kStages + st) * kTileBytes + (j - 4) * 4096);
     };
+#define APT_STAGE_FIRST(T0, T1)                                                                             \
+    _Pragma("unroll") for (int t_ = (T0); t_ < (T1); ++t_) {                                                \
+        _Pragma("unroll") for (int j_ = 0; j_ < kStageLoads; ++j_) stage_chunk(t_, t_, j_);                 \
+    }
 
     bool have = qi < q_end;
+    if (p.dbg & 4) {                 // experiment: stagger the workgroups of a queue over about one item
+        for (int i = 0; i < ((g >> 3) & 31); ++i) __builtin_amdgcn_s_sleep(127);
+    }
+    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g] = wall_clock64();
     if (have) {
         it = items[qi];
         lookup(it, ids);
         APT_MAKE_SOURCES(xsrc, wsrc, it, ids)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) stage_chunk(0, 0, j);
-#pragma unroll
-        for (int j = 0; j < 16; ++j) stage_chunk(1, 1, j);
+        APT_STAGE_FIRST(0, 4)
     }
 
     f32x16_t acc[4][4];
     uint4 fa[2][4], fb[2][4];
-#define APT_LOAD_FRAGS(SET, BUF, KS)                                                                        \
+#define APT_LOAD_FRAGS(SET, ST, KS, NI, NJ)                                                                 \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
-        fa[SET][i_] = *(const uint4*)(lds + (BUF) * kTileBytes + (a_addr[i_] ^ (32 * (KS))));               \
-        fb[SET][i_] = *(const uint4*)(lds + (BUF) * kTileBytes + (b_addr[i_] ^ (32 * (KS))));               \
+        if (i_ < NI) fa[SET][i_] = lds_read16((a_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
+        if (i_ < NJ) fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
     }
-#define APT_MFMA_ALL(SET, FULL)                                                                             \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
-        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                  \
-            if (FULL || (i_ < ni && j_ < nj)) acc[i_][j_] = mfma32<DT, EXP>(fa[SET][i_], fb[SET][j_], acc[i_][j_]); \
+#define APT_MFMA_ALL(SET, NI, NJ)                                                                           \
+    _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                     \
+        _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                                 \
+            acc[i_][j_] = mfma32<DT, EXP>(fa[SET][i_], fb[SET][j_], acc[i_][j_]);                           \
         }                                                                                                   \
     }
     // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
-#define APT_SCHED_STEP(FULL)                                                                                \
-    if (FULL) {                                                                                             \
-        _Pragma("unroll") for (int s_ = 0; s_ < 8; ++s_) {                                                  \
+#define APT_SCHED_STEP(NI, NJ)                                                                              \
+    {                                                                                                       \
+        _Pragma("unroll") for (int s_ = 0; s_ < NI + NJ; ++s_) {                                            \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
         }                                                                                                   \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x008, NI * NJ - NI - NJ, 0);                                  \
     }
-    // one k-tile: sub-steps 0..2 read the next sub-step's operands while they multiply; before
-    // the last sub-step all waves meet (their parts of the next k-tile have landed, this
-    // k-tile's stage is no longer read); then the next k-tile's first operands are read and,
-    // one copy per MFMA, the stage is refilled with the k-tile after next while the last
-    // sub-step multiplies.
-#define APT_K_TILE(BUF, STAGE, NEXT, FULL)                                                                  \
+    // one k-tile in stage ST: the first sub-step multiplies while the second one's operands are
+    // read; then all waves meet (their copies of the next k-tile have landed: at most WAITN
+    // younger copies may still be in flight; this k-tile's stage is no longer read, all its
+    // operands are in registers); then the next k-tile's first operands are read and, one copy
+    // per MFMA pair, this stage is refilled with k-tile kt + 4 while the second sub-step multiplies.
+#define APT_K_TILE(ST, STAGE, WAITN, NEXT, NI, NJ)                                                          \
     {                                                                                                       \
-        APT_LOAD_FRAGS(1, BUF, 1)                                                                           \
-        APT_MFMA_ALL(0, FULL)                                                                               \
-        APT_SCHED_STEP(FULL)                                                                                \
-        APT_LOAD_FRAGS(0, BUF, 2)                                                                           \
-        APT_MFMA_ALL(1, FULL)                                                                               \
-        APT_SCHED_STEP(FULL)                                                                                \
-        APT_LOAD_FRAGS(1, BUF, 3)                                                                           \
-        APT_MFMA_ALL(0, FULL)                                                                               \
-        APT_SCHED_STEP(FULL)                                                                                \
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                    \
-        __syncthreads();                                                                                    \
-        if (NEXT) { APT_LOAD_FRAGS(0, (BUF) ^ 1, 0) }                                                       \
+        APT_LOAD_FRAGS(1, ST, 1, NI, NJ)                                                                    \
+        APT_MFMA_ALL(0, NI, NJ)                                                                             \
+        APT_SCHED_STEP(NI, NJ)                                                                              \
+        if (NEXT) {                                                                                         \
+            wait_vmcnt<WAITN>();                                                                            \
+            __syncthreads();                                                                                \
+            APT_LOAD_FRAGS(0, ((ST) + 1) & 3, 0, NI, NJ)                                                    \
+        }                                                                                                   \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
-            _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                              \
-                if (STAGE && (EXP & 2) == 0) stage_chunk(kt + 2, BUF, i_ * 4 + j_);                         \
-                if (FULL || (i_ < ni && j_ < nj))                                                           \
-                    acc[i_][j_] = mfma32<DT, EXP>(fa[1][i_], fb[1][j_], acc[i_][j_]);                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                 \
+            _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                             \
+                const int m_ = i_ * NJ + j_;              /* 8 copies spread over the NI * NJ MFMAs */      \
+                if (STAGE && (EXP & 2) == 0) {                                                              \
+                    _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                              \
+                        if (c_ * (NI * NJ) / kStageLoads == m_) stage_chunk(kt + 4, ST, c_);                \
+                }                                                                                           \
+                acc[i_][j_] = mfma32<DT, EXP>(fa[1][i_], fb[1][j_], acc[i_][j_]);                           \
                 __builtin_amdgcn_sched_barrier(0);                                                          \
             }                                                                                               \
         }                                                                                                   \
     }
-#define APT_K_LOOP(FULL)                                                                                    \
+#define APT_K_LOOP(NI, NJ)                                                                                  \
     {                                                                                                       \
+        APT_LOAD_FRAGS(0, 0, 0, NI, NJ)                                                                     \
         int kt = 0;                                                                                         \
-        for (; kt + 2 < nkt; kt += 2) {                                                                     \
-            APT_K_TILE(0, true, true, FULL)                                                                 \
+        for (; kt + 8 <= nkt; kt += 4) {                                                                    \
+            APT_K_TILE(0, true, 2 * kStageLoads, true, NI, NJ)                                              \
             ++kt;                                                                                           \
-            APT_K_TILE(1, true, true, FULL)                                                                 \
-            --kt;                                                                                           \
+            APT_K_TILE(1, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            ++kt;                                                                                           \
+            APT_K_TILE(2, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            ++kt;                                                                                           \
+            APT_K_TILE(3, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            kt -= 3;                                                                                        \
         }                                                                                                   \
-        APT_K_TILE(0, false, true, FULL)                                                                    \
-        APT_K_TILE(1, false, false, FULL)                                                                   \
+        APT_K_TILE(0, false, 2 * kStageLoads, true, NI, NJ)   /* the last four k-tiles refill nothing */    \
+        APT_K_TILE(1, false, kStageLoads, true, NI, NJ)                                                     \
+        APT_K_TILE(2, false, 0, true, NI, NJ)                                                               \
+        APT_K_TILE(3, false, 0, false, NI, NJ)                                                              \
     }
 
     while (have) {
         const int r = it.x, h = it.y, t0 = it.z, nvalid = it.w - it.z;
-        // block ids of the next item: on their way while this item multiplies
+        // block ids of the next item: on their way while this item's first copies land
         const int nqi = qi + wpx;
         const bool have_next = nqi < q_end;
         int4 itn = it;
-        int32_t idsn[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) idsn[i] = 0;
+        int32_t idsn[4] = {0, 0, 0, 0};
         if (have_next) {
             itn = items[nqi];
             lookup(itn, idsn);
@@ -553,7 +575,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         // valid token blocks of this wave: blocks 2 b + th below ceil(nvalid / 32)
         const int nvb = (nvalid + 31) >> 5;
         const int nb = (nvb - th + 1) >> 1;
-        const int ni = mat == 0 ? 4 : nb, nj = mat == 0 ? nb : 4;
 
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -562,25 +583,30 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();                       // k-tiles 0 and 1 of this item are in LDS
-        // the next item's block ids have arrived; tell the compiler so, or the wait counts it
-        // would place inside the k loop for them would also wait for the staging copies
+        // everything issued so far has to land here: the loads the compiler keeps track of (or the
+        // wait counts it would place inside the k loop for them would also wait for the staging
+        // copies) and with them the first three k-tiles
+        wait_vmcnt<0>();
 #pragma unroll
-        for (int i = 0; i < 8; ++i) asm volatile("" ::"v"(idsn[i]));
+        for (int i = 0; i < 4; ++i) asm volatile("" ::"v"(idsn[i]));
         asm volatile("" ::"v"(itn.x), "v"(itn.y), "v"(itn.z), "v"(itn.w));
-        APT_LOAD_FRAGS(0, 0, 0)
-        if (nb == 4) APT_K_LOOP(true)
-        else APT_K_LOOP(false)
+        __syncthreads();
+        // the operand addresses must be in registers with nothing pending behind them (a reload the
+        // compiler still waits for inside the k loop would also wait for the staging copies)
+        asm volatile("" : "+v"(a_addr[0]), "+v"(a_addr[1]), "+v"(a_addr[2]), "+v"(a_addr[3]),
+                          "+v"(b_addr[0]), "+v"(b_addr[1]), "+v"(b_addr[2]), "+v"(b_addr[3]));
+        asm volatile("" : "+v"(xsrc[0]), "+v"(xsrc[1]), "+v"(xsrc[2]), "+v"(xsrc[3]), "+v"(wsrc));
+        // short tiles (at most two valid token blocks in this wave) multiply half of the tile only
+        if (nb > 2) APT_K_LOOP(4, 4)
+        else if (mat == 0) APT_K_LOOP(4, 2)
+        else APT_K_LOOP(2, 4)
 
-        // both stages are free now (every wave has passed the last barrier of the k loop):
-        // start the next item's first two k-tiles, then finish this item
+        // stages 0..2 are free now (every wave has passed the last barrier of the k loop; stage 3
+        // holds the last k-tile, which slower waves may still read): start the next item's first
+        // three k-tiles, then finish this item
         if (have_next) {
             APT_MAKE_SOURCES(xsrc, wsrc, itn, idsn)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) stage_chunk(0, 0, j);
-#pragma unroll
-            for (int j = 0; j < 16; ++j) stage_chunk(1, 1, j);
+            APT_STAGE_FIRST(0, 3)
         }
 
         // ---- epilogue.  Register e of tile (i, j): row 8 (e/4) + 4 half + e%4 of the A-side
@@ -623,6 +649,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             if (lane == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
         }
         __syncthreads();
+        if (have_next) APT_STAGE_FIRST(3, 4)      // every wave has left the k loop: stage 3 is free too
         if (mat == 1) {
             // V wave: rows = tokens of block 2 i + th, columns = channels 32 j + lane%32
             float o[4] = {0.f, 0.f, 0.f, 0.f};
@@ -631,14 +658,12 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     const float4 p4 = *(const float4*)(p_lds + (2 * i + th) * 32 + 8 * e4 + 4 * half);
-                    if (i < ni) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            o[j] = fmaf(acc[i][j][4 * e4 + 0], p4.x, o[j]);
-                            o[j] = fmaf(acc[i][j][4 * e4 + 1], p4.y, o[j]);
-                            o[j] = fmaf(acc[i][j][4 * e4 + 2], p4.z, o[j]);
-                            o[j] = fmaf(acc[i][j][4 * e4 + 3], p4.w, o[j]);
-                        }
+                    for (int j = 0; j < 4; ++j) {
+                        o[j] = fmaf(acc[i][j][4 * e4 + 0], p4.x, o[j]);
+                        o[j] = fmaf(acc[i][j][4 * e4 + 1], p4.y, o[j]);
+                        o[j] = fmaf(acc[i][j][4 * e4 + 2], p4.z, o[j]);
+                        o[j] = fmaf(acc[i][j][4 * e4 + 3], p4.w, o[j]);
                     }
                 }
             const float l = ml_lds[th * 2 + 1];
@@ -662,19 +687,22 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         it = itn;
     }
 #undef APT_K_LOOP
-#undef APT_MAKE_SOURCES
 #undef APT_K_TILE
 #undef APT_SCHED_STEP
 #undef APT_MFMA_ALL
 #undef APT_LOAD_FRAGS
+#undef APT_STAGE_FIRST
+#undef APT_MAKE_SOURCES
 
     // ---- then a share of the KV-kind items, longest first
     __syncthreads();
+    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g + 1] = wall_clock64();
     for (int i = p.n_hidden_items + g; i < p.n_items; i += G) {
         const int4 kv = items[i];
         kv_item<DT, HD>(p, kv.x, kv.y, kv.z, kv.w, lds);
         __syncthreads();
     }
+    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g + 2] = wall_clock64();
 }
 
 // ---------------------------------------------------------------------------------
@@ -733,13 +761,14 @@ __global__ __launch_bounds__(kThreads) void apt_pack_kernel(const uint16_t* W_K,
     // one thread per 16-byte unit; consecutive threads take consecutive channels so
     // that the strided reads of W coalesce
     const int nkt = d / kBK;
+    constexpr int units = kBK / 8;                      // 16-byte units per row
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t total = (int64_t)H * nkt * 256 * 8;
+    const int64_t total = (int64_t)H * nkt * 256 * units;
     if (gid >= total) return;
     const int row = (int)(gid % 256);
-    const int c = (int)((gid / 256) % 8);
-    const int kt = (int)((gid / 2048) % nkt);
-    const int h = (int)(gid / (2048 * (int64_t)nkt));
+    const int c = (int)((gid / 256) % units);
+    const int kt = (int)((gid / (256 * units)) % nkt);
+    const int h = (int)(gid / (256 * units * (int64_t)nkt));
     const uint16_t* W = row < 128 ? W_K : W_V;
     const int ch = h * 128 + (row & 127);
     const int k0 = kt * kBK + c * 8;
@@ -751,7 +780,7 @@ __global__ __launch_bounds__(kThreads) void apt_pack_kernel(const uint16_t* W_K,
     o.y = v[2] | ((uint32_t)v[3] << 16);
     o.z = v[4] | ((uint32_t)v[5] << 16);
     o.w = v[6] | ((uint32_t)v[7] << 16);
-    packed[((int64_t)h * nkt + kt) * 2048 + row * 8 + (c ^ swz(row))] = o;
+    packed[((int64_t)h * nkt + kt) * (256 * units) + row * units + (c ^ swz(row))] = o;
 }
 
 __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const uint4* src, int64_t n) {
@@ -864,7 +893,7 @@ extern "C" int apt_pack_weights(const apt_shape* s, const void* W_K, const void*
     if (!W_K || !W_V || !packed) return APT_EINVAL;
     if (rs.s.hidden_impl != APT_HIDDEN_MFMA) return APT_ESHAPE;
     const int d = rs.s.d_model, H = rs.s.n_heads;
-    const int64_t total = (int64_t)H * (d / kBK) * 2048;
+    const int64_t total = (int64_t)H * (d / kBK) * 256 * (kBK / 8);
     const int64_t blocks = (total + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(apt_pack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
                        (const uint16_t*)W_K, (const uint16_t*)W_V, (uint4*)packed, d, H);
@@ -939,7 +968,9 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     p.scale_log2e = rs.s.softmax_scale * 1.4426950408889634f;
     {
         static const int dbg = getenv("APT_DEBUG") ? atoi(getenv("APT_DEBUG")) : 0;
+        static const unsigned long long dbg_buf = getenv("APT_DEBUG_BUF") ? strtoull(getenv("APT_DEBUG_BUF"), nullptr, 0) : 0ull;
         p.dbg = dbg;
+        p.dbg_buf = (long long*)(uintptr_t)dbg_buf;
     }
     hipStream_t st = (hipStream_t)stream;
 

@@ -23,6 +23,13 @@ constexpr int kThreads = 256;
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read once (streamed past the caches)
+__device__ inline uint4 load16_stream(const char* p) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 struct ItemParams {
     const int32_t* plan;          // device blob
@@ -171,8 +178,8 @@ __device__ void kv_item(const ItemParams& p, int r, int h, int t0, int t1, char*
                 const int64_t kblk = __builtin_amdgcn_readlane(kid, pg);
                 const int64_t vblk = __builtin_amdgcn_readlane(vid, pg);
                 const int64_t off = head_off + (int64_t)(u & nl_mask) * 1024 + lane * 16;
-                kbuf[i] = *(const uint4*)(p.k_pages + kblk * blk_bytes + off);
-                vbuf[i] = *(const uint4*)(p.v_pages + vblk * blk_bytes + off);
+                kbuf[i] = load16_stream(p.k_pages + kblk * blk_bytes + off);
+                vbuf[i] = load16_stream(p.v_pages + vblk * blk_bytes + off);
             }
         }
     };
@@ -356,7 +363,8 @@ constexpr int kStageLoads = 8;                         // copies per wave and k-
 __host__ __device__ inline int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
 
 // EXP: 0 = production.  Timing experiments (wrong results), bit mask: 1 = no MFMAs,
-// 2 = no staging copies inside the k loop
+// 2 = no staging copies inside the k loop, 4 = no X staging copies inside the k loop,
+// 8 = no B-side operand reads inside the k loop, 16 = no W staging copies inside the k loop
 template <int DT, int EXP = 0> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
     if constexpr ((EXP & 1) != 0) {
         c[0] += __uint_as_float(a.x ^ b.x);      // keeps the operand reads alive
@@ -373,7 +381,6 @@ template <int DT, int EXP = 0> __device__ inline f32x16_t mfma32(const uint4& a,
 __device__ inline void gload_lds16(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
 }
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4_t;
 // 16-byte LDS read at an absolute LDS address (the dynamic LDS base is folded into the operand addresses once)
 __device__ inline uint4 lds_read16(uint32_t addr) {
@@ -486,7 +493,8 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #define APT_LOAD_FRAGS(SET, ST, KS, NI, NJ)                                                                 \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
         if (i_ < NI) fa[SET][i_] = lds_read16((a_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
-        if (i_ < NJ) fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
+        if (i_ < NJ && !((EXP & 8) && (KS) + (SET) > 0))                                                    \
+            fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);                       \
     }
 #define APT_MFMA_ALL(SET, NI, NJ)                                                                           \
     _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                     \
@@ -524,7 +532,8 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
                 const int m_ = i_ * NJ + j_;              /* 8 copies spread over the NI * NJ MFMAs */      \
                 if (STAGE && (EXP & 2) == 0) {                                                              \
                     _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                              \
-                        if (c_ * (NI * NJ) / kStageLoads == m_) stage_chunk(kt + 4, ST, c_);                \
+                        if (c_ * (NI * NJ) / kStageLoads == m_ && !((EXP & 4) && c_ >= 4) && !((EXP & 16) && c_ < 4)) \
+                            stage_chunk(kt + 4, ST, c_);                                                    \
                 }                                                                                           \
                 acc[i_][j_] = mfma32<DT, EXP>(fa[1][i_], fb[1][j_], acc[i_][j_]);                           \
                 __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -859,6 +868,10 @@ int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
         if constexpr (DT == 1) {     // timing experiments (wrong results), fp16 only
             if ((p.dbg >> 4) == 1) return launch_mfma<DT, 1>(p, st);
             if ((p.dbg >> 4) == 2) return launch_mfma<DT, 2>(p, st);
+            if ((p.dbg >> 4) == 4) return launch_mfma<DT, 4>(p, st);
+            if ((p.dbg >> 4) == 8) return launch_mfma<DT, 8>(p, st);
+            if ((p.dbg >> 4) == 16) return launch_mfma<DT, 16>(p, st);
+            if ((p.dbg >> 4) == 10) return launch_mfma<DT, 10>(p, st);
         }
         return launch_mfma<DT, 0>(p, st);
     }

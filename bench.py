@@ -102,28 +102,31 @@ def main():
         cfg = wl.with_ratio(cfg, args.hidden_ratio)
     t_gen = time.time()
     batch = wl.make_batch(cfg)
-    layer = wl.make_layer(batch, workers=min(16, os.cpu_count() or 8))
-    t_gen = time.time() - t_gen
-
+    nl = cfg.n_layers
     rn = DecodeRunner(batch, kv_chunk=args.kv_chunk)
-    dl = rn.upload(layer)
+    layer, dls = None, []
+    for li in range(nl):                      # every layer of the step is resident in HBM
+        layer = wl.make_layer(batch, layer=li, workers=min(16, os.cpu_count() or 8))
+        dls.append(rn.upload(layer, keep_raw_weights=(nl == 1)))
+    t_gen = time.time() - t_gen
+    dl = dls[-1]                              # `layer` is its host copy (cpu_baseline / parity sample)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
-        rn.plan()
-        rn.run(dl)
+        rn.run_step(dls)
     torch.cuda.synchronize()
 
-    ev = HipEvents(args.steps)
+    ev = HipEvents(args.steps * nl)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         rn.plan()
-        rn.run(dl, ev.pairs[i][0], ev.pairs[i][1])
+        for li in range(nl):
+            rn.run(dls[li], ev.pairs[i * nl + li][0], ev.pairs[i * nl + li][1])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps * nl)]
     ev.close()
     kern_avg_ms = float(np.mean(kern_ms))
 
@@ -131,7 +134,8 @@ def main():
     hidden_tokens = batch.hidden_tokens
     kv_tokens = batch.kv_tokens
     d, e = cfg.d_model, wl.ELEM_BYTES[cfg.dtype]
-    value = total_tokens / (ms_per_step * 1e-3)
+    # cached tokens per second per decode layer: a step of nl layers serves total_tokens in each layer
+    value = total_tokens * nl / (ms_per_step * 1e-3)
 
     # algorithmic work of the item kernel per launch
     flops = 4.0 * d * d * hidden_tokens                 # K and V projections of hidden-kind tokens
@@ -159,7 +163,9 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: d_model={d}, {cfg.n_heads} heads x {cfg.head_dim}, {cfg.dtype}, "
                                f"batch {batch.B}, ctx {cfg.len_dist}[{cfg.len_lo},{cfg.len_hi}], block {cfg.block_size}, "
-                               f"{int(round(100 * cfg.hidden_ratio))}% hidden-cache requests",
+                               f"{int(round(100 * cfg.hidden_ratio))}% hidden-cache requests"
+                               + (f", {nl} layers per step (one plan, {nl} attention calls)" if nl > 1 else ""),
+                   "layers_per_step": nl,
                    "total_tokens": total_tokens, "hidden_tokens": hidden_tokens, "kv_tokens": kv_tokens,
                    "n_items": int(rn.info.n_items), "n_hidden_items": int(rn.info.n_hidden_items),
                    "seed": cfg.seed, "input_gen_s": round(t_gen, 2)},
@@ -190,7 +196,18 @@ def main():
         result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
                                    "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
     if args.sweep:
-        result["sweep"] = [time_ratio(cfg, r, args) for r in (0.0, 0.25, 0.5, 0.75, 1.0)]
+        del rn, dls, dl
+        torch.cuda.empty_cache()
+        sweep = [time_ratio(cfg, r, args) for r in (0.0, 0.25, 0.5, 0.75, 1.0)]
+        result["sweep"] = sweep
+        # Section 4.2, Eq. 6 models the extra time of hidden-cache requests as t = rho * m, linear in
+        # their cached length: least-squares line of the item-kernel time over the hidden tokens
+        x = np.array([p["hidden_tokens"] for p in sweep], dtype=np.float64)
+        y = np.array([p["kernel_ms"] for p in sweep], dtype=np.float64)
+        slope, icpt = np.polyfit(x, y, 1)
+        resid = y - (slope * x + icpt)
+        result["rho_fit"] = {"rho_us_per_hidden_token": slope * 1e3, "intercept_ms": icpt,
+                             "r2": 1.0 - float((resid ** 2).sum() / ((y - y.mean()) ** 2).sum())}
     print(json.dumps(result))
 
 

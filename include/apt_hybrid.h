@@ -210,6 +210,25 @@ int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, cons
                                  void* ev_begin, void* ev_end);
 
 /*
+ * Cache append: writes the vectors of the token just processed into the request's cache
+ * blocks, with the layout change fused into the write (the paper's block-wise cache I/O
+ * kernel, Section 5.1; block placement per Section 4.3).  For request r with
+ * n = ctx_lens[r] tokens AFTER the append, position n-1 (block entry (n-1)/block_size, slot
+ * (n-1)%block_size) receives
+ *     hidden kind: x_new[r][0..d_model)                      -> hidden block [slot][d_model]
+ *     KV kind:     k_new[r][head][0..head_dim), v_new[...]   -> K / V block [head][slot][head_dim]
+ * All pointers are device memory; ctx_lens_dev int32 [B], cache_kind_dev uint8 [B];
+ * x_new may be NULL if no request is hidden-kind, k_new/v_new if none is KV-kind (the kernel
+ * does not check the kinds against NULL: pass what the batch needs).  Elements are copied
+ * bit for bit.  One launch on `stream`.  Run it before apt_hybrid_decode_attn of the same
+ * step (ctx_lens counts the current token).
+ * Errors: APT_EINVAL (B < 1, missing tables or all three sources NULL), APT_ESHAPE, APT_EDTYPE, APT_EHIP.
+ */
+int apt_cache_append(const apt_shape* s, int B, const void* x_new, const void* k_new, const void* v_new,
+                     void* k_pages, void* v_pages, void* hidden_pages, const int32_t* block_tables,
+                     const int32_t* ctx_lens_dev, const uint8_t* cache_kind_dev, void* stream);
+
+/*
  * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16; device
  * pointers, 16-byte aligned).  Exists so that hardware traffic counters can be
  * calibrated against a kernel of known traffic (reads `bytes`, writes `bytes`).

@@ -269,3 +269,40 @@ int apt_oracle_merge(int n_splits, int hd, const double* m, const double* l, con
     for (int c = 0; c < hd; ++c) out[c] /= ls;
     return 0;
 }
+
+/*
+ * Cache append (Section 5.1: the cache engine writes the vectors of the token just
+ * processed into the request's blocks; Section 4.3 for where they go).  For request r
+ * with n = ctx_lens[r] tokens after the append, position n-1 receives
+ *   hidden kind: x_new[r][0..d)             -> hidden block [slot][d]
+ *   KV kind:     k_new[r][h][c], v_new[...] -> K block, V block [head][slot][head_dim]
+ * Bytes are copied unchanged (element size from the dtype).  Returns 0, -1 on a bad argument.
+ */
+int apt_oracle_append(const oracle_shape* s, int B, const void* x_new, const void* k_new, const void* v_new,
+                      void* k_pages, void* v_pages, void* hidden_pages,
+                      const int32_t* block_tables, const int32_t* ctx_lens, const uint8_t* cache_kind) {
+    const int d = s->d_model, H = s->n_heads, hd = s->head_dim, bs = s->block_size;
+    const int eb = s->dtype == ORACLE_F32 ? 4 : 2;
+    const int64_t blk_elems = (int64_t)bs * d;
+    for (int r = 0; r < B; ++r) {
+        if (ctx_lens[r] < 1 || cache_kind[r] > 1) return -1;
+        const int j = ctx_lens[r] - 1;
+        int32_t b0, b1, slot;
+        apt_oracle_locate(block_tables, s->max_blocks, bs, r, 0, j, &b0, &slot);
+        if (cache_kind[r] == ORACLE_HIDDEN) {
+            for (int i = 0; i < d; ++i)
+                memcpy((char*)hidden_pages + (b0 * blk_elems + (int64_t)slot * d + i) * eb,
+                       (const char*)x_new + ((int64_t)r * d + i) * eb, eb);
+        } else {
+            apt_oracle_locate(block_tables, s->max_blocks, bs, r, 1, j, &b1, &slot);
+            for (int h = 0; h < H; ++h)
+                for (int c = 0; c < hd; ++c) {
+                    const int64_t off = ((int64_t)h * bs + slot) * hd + c;
+                    const int64_t src = ((int64_t)r * H + h) * hd + c;
+                    memcpy((char*)k_pages + (b0 * blk_elems + off) * eb, (const char*)k_new + src * eb, eb);
+                    memcpy((char*)v_pages + (b1 * blk_elems + off) * eb, (const char*)v_new + src * eb, eb);
+                }
+        }
+    }
+    return 0;
+}

@@ -24,7 +24,7 @@ def lib():
         path = _build.build(force=False)
         _lib = C.CDLL(path)
         _lib.apt_oracle_threads.restype = C.c_int
-        for name in ("apt_oracle_attn", "apt_oracle_partial", "apt_oracle_merge"):
+        for name in ("apt_oracle_attn", "apt_oracle_partial", "apt_oracle_merge", "apt_oracle_append"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -100,3 +100,15 @@ def merge(m, l, acc):
     if rc != 0:
         raise ValueError("apt_oracle_merge: bad argument")
     return out
+
+
+def append(shape, x_new, k_new, v_new, k_pages, v_pages, hidden_pages, block_tables, ctx_lens, cache_kind):
+    """In-place cache append of the current token's vectors (position ctx_lens[r] - 1)."""
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    cache_kind = np.ascontiguousarray(cache_kind, dtype=np.uint8)
+    block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+    rc = lib().apt_oracle_append(C.byref(shape), C.c_int(len(ctx_lens)), _p(x_new), _p(k_new), _p(v_new),
+                                 _p(k_pages), _p(v_pages), _p(hidden_pages), _p(block_tables), _p(ctx_lens),
+                                 _p(cache_kind))
+    if rc != 0:
+        raise ValueError("apt_oracle_append: bad argument")

@@ -22,7 +22,7 @@ DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 
 EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt_plan_get_info", "apt_plan_upload",
            "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
-           "apt_hybrid_decode_attn_timed", "apt_copy_bytes", "apt_probe_mfma"]
+           "apt_hybrid_decode_attn_timed", "apt_cache_append", "apt_copy_bytes", "apt_probe_mfma"]
 
 
 class apt_shape(C.Structure):
@@ -155,6 +155,13 @@ def apt_hybrid_decode_attn_timed(shape, plan_host, plan_dev, q, k_pages, v_pages
                                               _ptr(W_packed), _ptr(b_K), _ptr(b_V), _ptr(block_tables), _ptr(out),
                                               _ptr(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream),
                                               _ptr(ev_begin), _ptr(ev_end)), "apt_hybrid_decode_attn_timed")
+
+
+def apt_cache_append(shape, B, x_new, k_new, v_new, k_pages, v_pages, hidden_pages, block_tables, ctx_lens_dev,
+                     cache_kind_dev, stream=0):
+    _check(lib().apt_cache_append(C.byref(shape), C.c_int(B), _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(k_pages),
+                                  _ptr(v_pages), _ptr(hidden_pages), _ptr(block_tables), _ptr(ctx_lens_dev),
+                                  _ptr(cache_kind_dev), C.c_void_p(stream)), "apt_cache_append")
 
 
 def apt_copy_bytes(dst, src, nbytes, stream=0):

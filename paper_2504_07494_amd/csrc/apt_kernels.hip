@@ -792,6 +792,37 @@ __global__ __launch_bounds__(kThreads) void apt_pack_kernel(const uint16_t* W_K,
     packed[((int64_t)h * nkt + kt) * (256 * units) + row * units + (c ^ swz(row))] = o;
 }
 
+// Cache append: one workgroup per request, 16-byte units.  A unit never straddles a head
+// (head_dim * element size is a multiple of 16).
+__global__ __launch_bounds__(kThreads) void apt_append_kernel(const char* x_new, const char* k_new, const char* v_new,
+                                                              char* k_pages, char* v_pages, char* hidden_pages,
+                                                              const int32_t* block_tables, const int32_t* ctx_lens,
+                                                              const uint8_t* cache_kind, int d, int hd, int bs, int log2_bs,
+                                                              int max_blocks, int eb) {
+    const int r = blockIdx.x;
+    const int j = ctx_lens[r] - 1;
+    if (j < 0) return;
+    const int slot = j & (bs - 1);
+    const int64_t blk_bytes = (int64_t)bs * d * eb;
+    const int row_units = d * eb / 16;
+    const int64_t e0 = (int64_t)r * 2 * max_blocks + (j >> log2_bs);
+    if (cache_kind[r] == APT_KIND_HIDDEN) {
+        char* dst = hidden_pages + (int64_t)block_tables[e0] * blk_bytes + (int64_t)slot * d * eb;
+        for (int u = threadIdx.x; u < row_units; u += kThreads)
+            *(uint4*)(dst + (int64_t)u * 16) = *(const uint4*)(x_new + ((int64_t)r * row_units + u) * 16);
+    } else {
+        char* kd = k_pages + (int64_t)block_tables[e0] * blk_bytes;
+        char* vd = v_pages + (int64_t)block_tables[e0 + max_blocks] * blk_bytes;
+        const int head_units = hd * eb / 16;
+        for (int u = threadIdx.x; u < row_units; u += kThreads) {
+            const int h = u / head_units, cu = u % head_units;
+            const int64_t off = (((int64_t)h * bs + slot) * hd) * eb + (int64_t)cu * 16;
+            *(uint4*)(kd + off) = *(const uint4*)(k_new + ((int64_t)r * row_units + u) * 16);
+            *(uint4*)(vd + off) = *(const uint4*)(v_new + ((int64_t)r * row_units + u) * 16);
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const uint4* src, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
@@ -910,6 +941,24 @@ extern "C" int apt_pack_weights(const apt_shape* s, const void* W_K, const void*
     const int64_t blocks = (total + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(apt_pack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
                        (const uint16_t*)W_K, (const uint16_t*)W_V, (uint4*)packed, d, H);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_cache_append(const apt_shape* s, int B, const void* x_new, const void* k_new, const void* v_new,
+                                void* k_pages, void* v_pages, void* hidden_pages, const int32_t* block_tables,
+                                const int32_t* ctx_lens_dev, const uint8_t* cache_kind_dev, void* stream) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (B < 1 || !block_tables || !ctx_lens_dev || !cache_kind_dev) return APT_EINVAL;
+    if (!x_new && !k_new && !v_new) return APT_EINVAL;
+    if ((x_new && !hidden_pages) || ((k_new || v_new) && (!k_new || !v_new || !k_pages || !v_pages))) return APT_EINVAL;
+    int log2_bs = 0;
+    while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
+    hipLaunchKernelGGL(apt_append_kernel, dim3(B), dim3(kThreads), 0, (hipStream_t)stream, (const char*)x_new,
+                       (const char*)k_new, (const char*)v_new, (char*)k_pages, (char*)v_pages, (char*)hidden_pages,
+                       block_tables, ctx_lens_dev, cache_kind_dev, rs.s.d_model, rs.s.head_dim, rs.s.block_size, log2_bs,
+                       rs.s.max_blocks_per_req, rs.elem_bytes);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 

@@ -21,7 +21,8 @@ def _to_dev(raw: np.ndarray, device) -> torch.Tensor:
 
 
 class DeviceLayer:
-    def __init__(self, runner: "DecodeRunner", layer: wl.Layer, separate_pools: bool = False):
+    def __init__(self, runner: "DecodeRunner", layer: wl.Layer, separate_pools: bool = False,
+                 keep_raw_weights: bool = True):
         dev = runner.device
         self.pool = _to_dev(layer.pool, dev)
         if separate_pools:
@@ -39,6 +40,9 @@ class DeviceLayer:
             self.W_packed = torch.empty(nbytes, dtype=torch.uint8, device=dev)
             ab.apt_pack_weights(runner.shape, self.W_K, self.W_V, self.W_packed,
                                 torch.cuda.current_stream(dev).cuda_stream)
+            if not keep_raw_weights:          # the MFMA kernel reads only the packed copy
+                torch.cuda.current_stream(dev).synchronize()
+                self.W_K = self.W_V = None
 
 
 class DecodeRunner:
@@ -78,22 +82,31 @@ class DecodeRunner:
             self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=self.device)
         return self.info
 
-    def upload(self, layer: wl.Layer, separate_pools: bool = False) -> DeviceLayer:
-        return DeviceLayer(self, layer, separate_pools)
+    def upload(self, layer: wl.Layer, separate_pools: bool = False, keep_raw_weights: bool = True) -> DeviceLayer:
+        return DeviceLayer(self, layer, separate_pools, keep_raw_weights)
 
-    def run(self, dl: DeviceLayer, ev_begin=None, ev_end=None) -> torch.Tensor:
+    def run(self, dl: DeviceLayer, ev_begin=None, ev_end=None, out=None) -> torch.Tensor:
         """a2-a4: the attention call for one layer (asynchronous on the current stream).
-        ev_begin / ev_end: optional raw hipEvent_t handles recorded around the item kernel."""
+        ev_begin / ev_end: optional raw hipEvent_t handles recorded around the item kernel.
+        out: optional output tensor of this layer (default: the runner's own buffer)."""
+        out = self.out if out is None else out
         if ev_begin is None and ev_end is None:
             ab.apt_hybrid_decode_attn(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool, dl.pool,
-                                      dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables, self.out,
+                                      dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables, out,
                                       self.workspace, self.workspace.numel(), self.stream())
         else:
             ab.apt_hybrid_decode_attn_timed(self.shape, self.plan_host, self.plan_dev, dl.q, dl.k_pool, dl.v_pool,
                                             dl.pool, dl.W_K, dl.W_V, dl.W_packed, dl.b_K, dl.b_V, self.block_tables,
-                                            self.out, self.workspace, self.workspace.numel(), self.stream(),
+                                            out, self.workspace, self.workspace.numel(), self.stream(),
                                             ev_begin, ev_end)
-        return self.out
+        return out
+
+    def run_step(self, layers, outs=None):
+        """One decode step over several layers: the plan is made once (lengths and cache kinds are per
+        request, the same in every layer), then one attention call per layer."""
+        self.plan()
+        for i, dl in enumerate(layers):
+            self.run(dl, out=None if outs is None else outs[i])
 
     def out_f64(self) -> np.ndarray:
         torch.cuda.synchronize(self.device)

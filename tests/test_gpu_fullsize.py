@@ -69,3 +69,54 @@ def test_opt30b_layer_permuted_pages(oracle):
 @pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
 def test_opt66b_layer_ratio_sweep(oracle, ratio):
     _run_and_check(oracle, wl.with_ratio(wl.CONFIGS["opt66b"], ratio), n_random=10)
+
+
+@pytest.mark.timeout(900)
+def test_full_decode_step_forty_layers_bf16(oracle):
+    """The 40-layer OPT-13B-shaped step: every layer's pool, weights and queries resident in
+    HBM at once (about 150 GB), one plan, 40 attention calls; three layers (first, middle,
+    last) are checked on sampled (request, head) pairs, all layers for finiteness."""
+    import torch
+    from paper_2504_07494_amd.harness import DecodeRunner
+    cfg = wl.CONFIGS["opt13b_step"]
+    free, total = torch.cuda.mem_get_info()
+    batch = wl.make_batch(cfg)
+    need = cfg.n_layers * (batch.n_pool_blocks * cfg.block_size * cfg.d_model * 2 + 4 * cfg.d_model ** 2 * 2)
+    if free < need * 1.05:
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of free HBM, {free / 2**30:.0f} GiB available")
+    print(f"[case] full step {cfg.name}: {cfg.n_layers} layers, {batch.total_tokens} tokens/layer, "
+          f"{need / 2**30:.0f} GiB resident", flush=True)
+    rn = DecodeRunner(batch)
+    checked = {0, cfg.n_layers // 2, cfg.n_layers - 1}
+    kept, layers = {}, []
+    for li in range(cfg.n_layers):
+        layer = wl.make_layer(batch, layer=li, workers=16)
+        layers.append(rn.upload(layer, keep_raw_weights=False))
+        if li in checked:
+            kept[li] = layer
+        if li % 8 == 0:
+            print(f"  layer {li} resident", flush=True)
+        del layer
+    outs = [torch.empty_like(rn.out) for _ in range(cfg.n_layers)]
+    rn.run_step(layers, outs)
+    torch.cuda.synchronize()
+    first = [o.clone() for o in outs]
+    pairs = _sample_pairs(batch, 12, cfg.seed)
+    for li in sorted(checked):
+        got = outs[li].float().cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got))
+        want = oracle_attn(oracle, batch, kept[li], pairs=pairs)
+        sel = got[[p[0] for p in pairs], [p[1] for p in pairs]]
+        err = np.abs(sel - want)
+        big = np.abs(want) >= 1e-2
+        a, r = float(err.max()), float((err[big] / np.abs(want[big])).max())
+        print(f"[parity] {cfg.name} layer {li}: {len(pairs)} pairs, max_abs={a:.3e} max_rel={r:.3e}", flush=True)
+        assert a <= 2e-3 and r <= 1e-2
+    for o in outs:
+        assert bool(torch.isfinite(o).all())
+    # layers differ (per-layer weights, pools and queries) and the step is reproducible
+    assert not torch.equal(outs[0], outs[1])
+    rn.run_step(layers, outs)
+    torch.cuda.synchronize()
+    for a, b in zip(first, outs):
+        assert torch.equal(a, b)

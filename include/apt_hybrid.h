@@ -24,7 +24,8 @@
  *     allocates no device memory and keeps no state between calls.
  *   - Launching functions take a HIP stream as void* (NULL = default stream) and
  *     return after enqueueing; inputs are read-only, only `out`, `workspace`,
- *     and `packed` (apt_pack_weights) are written.
+ *     `packed` (apt_pack_weights), the cache pools (apt_cache_append) and one
+ *     counter word of `plan_dev` are written.
  *   - Arguments are validated on the host before anything is launched.  Block
  *     ids inside block_tables are NOT range-checked on the device; use
  *     apt_validate_host() on a host copy.
@@ -175,7 +176,11 @@ int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void*
 
 /*
  * The decode attention step for one layer (Eq. 1-3 over both cache kinds).
- *   plan_host / plan_dev   the blob from apt_plan and its device copy
+ *   plan_host / plan_dev   the blob from apt_plan and its device copy.  One word of the device
+ *               copy (a ticket counter that hands out KV-kind items inside the launch) is
+ *               written by the item kernel and reset by the merge kernel, so two calls that
+ *               share one plan_dev must be ordered on one stream (calls for successive layers
+ *               are); everything else in it is read-only
  *   q, k_pages, v_pages, hidden_pages, b_K, b_V, block_tables, out   device, see layout
  *   W_K, W_V    device, raw [d_in][d_out]; read only by the plain-ALU hidden kernel
  *               (may be NULL when the resolved hidden_impl is MFMA or no request is
@@ -190,7 +195,7 @@ int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void*
  * Errors: APT_EINVAL (null pointer that is needed), APT_EWORKSPACE, APT_ESHAPE,
  * APT_EDTYPE, APT_EHIP (launch failure; nothing is written in the other cases).
  */
-int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
+int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev,
                            const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
                            const void* W_K, const void* W_V, const void* W_packed,
                            const void* b_K, const void* b_V, const int32_t* block_tables,
@@ -202,7 +207,7 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void
  * timing enabled; either may be NULL) are recorded on `stream` immediately before and
  * after the item kernel, so that a caller can time that kernel apart from the merge.
  */
-int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, const void* plan_dev,
+int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
                                  const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
                                  const void* W_K, const void* W_V, const void* W_packed,
                                  const void* b_K, const void* b_V, const int32_t* block_tables,

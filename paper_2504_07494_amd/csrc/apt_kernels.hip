@@ -33,6 +33,7 @@ __device__ inline uint4 load16_stream(const char* p) {
 
 struct ItemParams {
     const int32_t* plan;          // device blob
+    int32_t* kv_ticket;           // device blob word APT_PW_KV_TICKET: next KV-kind item of the persistent launch
     const char* q;
     const char* k_pages;
     const char* v_pages;
@@ -129,7 +130,7 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr int kKvUnits = 4;   // 1 KB loads of K (and of V) per pipeline stage
 
 template <int DT, int HD>
-__device__ void kv_item(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+__device__ __forceinline__ void kv_item(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
     constexpr int EB = Elt<DT>::bytes;
     constexpr int EPL = Elt<DT>::per16;          // elements per lane per load
     constexpr int LPR = HD * EB / 16;            // lanes per row
@@ -258,7 +259,7 @@ __device__ void kv_item(const ItemParams& p, int r, int h, int t0, int t1, char*
 // does not cover).  chunk <= 64 tokens.
 // ---------------------------------------------------------------------------------
 template <int DT, int HD>
-__device__ void hidden_item_valu(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
+__device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int h, int t0, int t1, char* lds) {
     constexpr int NG = kThreads / HD;     // token groups
     constexpr int TJ = 4;                 // tokens per pass of a thread
     constexpr int LD = HD + 1;
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     }
     // copies chunk j (0..3: weights, 4..7: X rows) of this wave's share of k-tile kt into stage st
     auto stage_chunk = [&](int kt, int st, int j) {
-        if (p.dbg & 1) kt &= 3;      // experiment: re-read the first four k-tiles (cache-resident operands)
+        if constexpr ((EXP & 32) != 0) kt &= 3;      // experiment: re-read the first four k-tiles (cache-resident operands)
         if (j < 4)
             gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + st * kTileBytes + j * 4096);
         else
@@ -477,9 +478,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     }
 
     bool have = qi < q_end;
-    if (p.dbg & 4) {                 // experiment: stagger the workgroups of a queue over about one item
-        for (int i = 0; i < ((g >> 3) & 31); ++i) __builtin_amdgcn_s_sleep(127);
-    }
     if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g] = wall_clock64();
     if (have) {
         it = items[qi];
@@ -540,8 +538,14 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             }                                                                                               \
         }                                                                                                   \
     }
+    // The addresses used inside the k loop must be in registers with nothing pending behind them
+    // when the loop starts: a reload the compiler still waits for inside the loop would also wait
+    // for the staging copies.
 #define APT_K_LOOP(NI, NJ)                                                                                  \
     {                                                                                                       \
+        asm volatile("" : "+v"(a_addr[0]), "+v"(a_addr[1]), "+v"(a_addr[2]), "+v"(a_addr[3]),               \
+                          "+v"(b_addr[0]), "+v"(b_addr[1]), "+v"(b_addr[2]), "+v"(b_addr[3]));              \
+        asm volatile("" : "+v"(xsrc[0]), "+v"(xsrc[1]), "+v"(xsrc[2]), "+v"(xsrc[3]), "+v"(wsrc));          \
         APT_LOAD_FRAGS(0, 0, 0, NI, NJ)                                                                     \
         int kt = 0;                                                                                         \
         for (; kt + 8 <= nkt; kt += 4) {                                                                    \
@@ -600,15 +604,18 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         for (int i = 0; i < 4; ++i) asm volatile("" ::"v"(idsn[i]));
         asm volatile("" ::"v"(itn.x), "v"(itn.y), "v"(itn.z), "v"(itn.w));
         __syncthreads();
-        // the operand addresses must be in registers with nothing pending behind them (a reload the
-        // compiler still waits for inside the k loop would also wait for the staging copies)
-        asm volatile("" : "+v"(a_addr[0]), "+v"(a_addr[1]), "+v"(a_addr[2]), "+v"(a_addr[3]),
-                          "+v"(b_addr[0]), "+v"(b_addr[1]), "+v"(b_addr[2]), "+v"(b_addr[3]));
-        asm volatile("" : "+v"(xsrc[0]), "+v"(xsrc[1]), "+v"(xsrc[2]), "+v"(xsrc[3]), "+v"(wsrc));
-        // short tiles (at most two valid token blocks in this wave) multiply half of the tile only
-        if (nb > 2) APT_K_LOOP(4, 4)
-        else if (mat == 0) APT_K_LOOP(4, 2)
-        else APT_K_LOOP(2, 4)
+        // a short tile multiplies only the token blocks that hold valid tokens (at least one, so
+        // that every wave runs the same barriers)
+        if (nb == 4) APT_K_LOOP(4, 4)
+        else if (mat == 0) {
+            if (nb == 3) APT_K_LOOP(4, 3)
+            else if (nb == 2) APT_K_LOOP(4, 2)
+            else APT_K_LOOP(4, 1)
+        } else {
+            if (nb == 3) APT_K_LOOP(3, 4)
+            else if (nb == 2) APT_K_LOOP(2, 4)
+            else APT_K_LOOP(1, 4)
+        }
 
         // stages 0..2 are free now (every wave has passed the last barrier of the k loop; stage 3
         // holds the last k-tile, which slower waves may still read): start the next item's first
@@ -706,7 +713,13 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     // ---- then a share of the KV-kind items, longest first
     __syncthreads();
     if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g + 1] = wall_clock64();
-    for (int i = p.n_hidden_items + g; i < p.n_items; i += G) {
+    // handed out one by one, so that workgroups that finish their hidden-kind share early take more
+    int* ticket_lds = (int*)(lds + 2 * kStages * kTileBytes);
+    for (;;) {
+        if (tid == 0) *ticket_lds = atomicAdd(p.kv_ticket, 1);
+        __syncthreads();
+        const int i = p.n_hidden_items + *ticket_lds;
+        if (i >= p.n_items) break;
         const int4 kv = items[i];
         kv_item<DT, HD>(p, kv.x, kv.y, kv.z, kv.w, lds);
         __syncthreads();
@@ -736,8 +749,9 @@ __global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
 // ---------------------------------------------------------------------------------
 template <int ODT>
 __global__ __launch_bounds__(kThreads) void apt_merge_kernel(const int32_t* plan, const float* ws_acc, const float2* ws_ml,
-                                                             char* out, int B, int H, int HD) {
+                                                             char* out, int B, int H, int HD, int32_t* kv_ticket) {
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid == 0) *kv_ticket = 0;           // the item kernel of this call is done: ready for the next call
     if (gid >= (int64_t)B * H * HD) return;
     const int c = (int)(gid % HD);
     const int64_t pair = gid / HD;
@@ -899,10 +913,7 @@ int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
         if constexpr (DT == 1) {     // timing experiments (wrong results), fp16 only
             if ((p.dbg >> 4) == 1) return launch_mfma<DT, 1>(p, st);
             if ((p.dbg >> 4) == 2) return launch_mfma<DT, 2>(p, st);
-            if ((p.dbg >> 4) == 4) return launch_mfma<DT, 4>(p, st);
-            if ((p.dbg >> 4) == 8) return launch_mfma<DT, 8>(p, st);
-            if ((p.dbg >> 4) == 16) return launch_mfma<DT, 16>(p, st);
-            if ((p.dbg >> 4) == 10) return launch_mfma<DT, 10>(p, st);
+            if ((p.dbg >> 4) == 32) return launch_mfma<DT, 32>(p, st);
         }
         return launch_mfma<DT, 0>(p, st);
     }
@@ -978,7 +989,7 @@ extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, void* stre
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, const void* plan_dev,
+extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
                                             const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
                                             const void* W_K, const void* W_V, const void* W_packed,
                                             const void* b_K, const void* b_V, const int32_t* block_tables,
@@ -1010,6 +1021,7 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
 
     ItemParams p;
     p.plan = (const int32_t*)plan_dev;
+    p.kv_ticket = (int32_t*)plan_dev + APT_PW_KV_TICKET;
     p.q = (const char*)q;
     p.k_pages = (const char*)k_pages;
     p.v_pages = (const char*)v_pages;
@@ -1050,15 +1062,15 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     const int64_t total = (int64_t)B * rs.s.n_heads * hd;
     const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
     if (rs.s.out_dtype == APT_F32)
-        hipLaunchKernelGGL(apt_merge_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+        hipLaunchKernelGGL(apt_merge_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
     else if (rs.s.out_dtype == APT_F16)
-        hipLaunchKernelGGL(apt_merge_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+        hipLaunchKernelGGL(apt_merge_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
     else
-        hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd);
+        hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, const void* plan_dev,
+extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev,
                                       const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
                                       const void* W_K, const void* W_V, const void* W_packed,
                                       const void* b_K, const void* b_V, const int32_t* block_tables,

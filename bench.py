@@ -268,18 +268,20 @@ def run_probe(args):
         print(json.dumps({"probe": "copy", "bytes_read": n, "bytes_written": n, "ms": ms,
                           "read_plus_write_GBs": 2 * n / ms / 1e6}))
     else:
-        nwg, iters = 1024, 5000
+        nwg, iters = 1024, 20000
         out = torch.empty(nwg * 256, dtype=torch.float32, device=dev)
-        for _ in range(args.warmup):
-            ab.apt_probe_mfma(out, nwg, iters, st)
-        a.record()
-        for _ in range(args.steps):
-            ab.apt_probe_mfma(out, nwg, iters, st)
-        b.record()
-        torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / args.steps
-        print(json.dumps({"probe": "mfma", "flops": nwg * 4 * iters * 16 * 32768.0, "ms": ms,
-                          "TFLOPs": nwg * 4 * iters * 16 * 32768.0 / ms / 1e9}))
+        res = {"probe": "mfma", "flops": nwg * 4 * iters * 16 * 32768.0}
+        for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+            for _ in range(args.warmup):
+                ab.apt_probe_mfma(out, nwg, iters, rnd, st)
+            a.record()
+            for _ in range(args.steps):
+                ab.apt_probe_mfma(out, nwg, iters, rnd, st)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / args.steps
+            res[name] = {"ms": ms, "TFLOPs": res["flops"] / ms / 1e9}
+        print(json.dumps(res))
 
 
 if __name__ == "__main__":

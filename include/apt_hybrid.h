@@ -169,7 +169,7 @@ int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens_host, const ui
  * bytes = 2 * d_model^2 elements.  Layout of `packed`, in 16-byte units of 8 elements:
  *   [head][k-tile of 32 inputs][row 0..255][unit 0..3], row < 128: W_K output channel
  *   head*128+row, row >= 128: W_V output channel head*128+row-128; the unit holding
- *   inputs k-tile*32 + 8*c .. +7 sits at position c ^ (((row >> 1) ^ (row >> 3)) & 3).
+ *   inputs k-tile*32 + 8*c .. +7 sits at position c ^ ((row >> 2) & 3).
  */
 int apt_packed_weight_bytes(const apt_shape* s, size_t* bytes);
 int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void* packed, void* stream);
@@ -243,11 +243,14 @@ int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
 /*
  * Register-only fp16 MFMA loop (no memory traffic): n_workgroups workgroups of 256
  * threads, each wave issuing iters * 16 independent 32x32x16 MFMAs
- * (n_workgroups * 4 * iters * 16 * 32768 flops in total).  `out` (device) receives
- * n_workgroups * 256 floats.  Exists to measure the rate the matrix pipes sustain on
- * the device at hand, as context for the MFMA roofline fraction.
+ * (n_workgroups * 4 * iters * 16 * 32768 flops in total).  random_operands = 0: constant
+ * operands; != 0: operands of magnitude ~1 with random mantissas and signs, which is what
+ * the multipliers see with real data (the sustained clock under the board's power limit
+ * depends on it).  `out` (device) receives n_workgroups * 256 floats.  Exists to measure the
+ * rate the matrix pipes sustain on the device at hand, as context for the MFMA roofline
+ * fraction.
  */
-int apt_probe_mfma(void* out, int n_workgroups, int iters, void* stream);
+int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, void* stream);
 
 #ifdef __cplusplus
 }

@@ -361,7 +361,8 @@ constexpr int kMfmaScratch = 4096;                     // epilogue scratch behin
 constexpr int kMfmaLds = 2 * kStages * kTileBytes + kMfmaScratch;
 constexpr int kStageLoads = 8;                         // copies per wave and k-tile: 4 of W, 4 of X
 
-__host__ __device__ inline int swz(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+// (row >> 2) & 3: measured free of LDS bank conflicts for the 16-byte operand reads of 64-byte rows
+__host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
 
 // EXP: 0 = production.  Timing experiments (wrong results), bit mask: 1 = no MFMAs,
 // 2 = no staging copies inside the k loop, 4 = no X staging copies inside the k loop,
@@ -844,18 +845,32 @@ __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const ui
 }
 
 // Register-only MFMA loop: 4 waves per workgroup, 16 independent 32x32x16 fp16 MFMAs per
-// iteration and wave, no memory traffic.  Measures the rate the matrix pipes sustain.
-__global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, int iters) {
+// iteration and wave, no memory traffic.  Measures the rate the matrix pipes sustain.  With
+// random_operands the 8 operand registers hold values of magnitude ~1 with random mantissas and
+// signs (what real activations look like to the multipliers) instead of constants.
+__global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, int iters, int random_operands) {
     f32x16_t acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-    uint4 a = make_uint4(threadIdx.x, 0x3c003c00u, 0x3c003c00u, blockIdx.x);
-    uint4 b = make_uint4(0x3c003c00u, threadIdx.x, 0x38003800u, 0x3c003c00u);
+    uint4 a[4], b[4];
+    uint32_t x = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u + 12345u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);
+        b[i] = make_uint4(0x38003800u, 0x38003800u, 0x38003800u, 0x38003800u);
+        if (random_operands) {
+            auto nxt = [&]() { x ^= x << 13; x ^= x >> 17; x ^= x << 5; return (x & 0x83ff83ffu) | 0x3c003c00u; };
+            a[i] = make_uint4(nxt(), nxt(), nxt(), nxt());
+            b[i] = make_uint4(nxt(), nxt(), nxt(), nxt());
+        }
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = mfma32<1>(a, b, acc[i]);
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i * 4 + j] = mfma32<1>(a[i], b[j], acc[i * 4 + j]);
     }
     float sum = 0.f;
 #pragma unroll
@@ -983,9 +998,10 @@ extern "C" int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* st
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, void* stream) {
+extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, void* stream) {
     if (!out || n_workgroups < 1 || iters < 1) return APT_EINVAL;
-    hipLaunchKernelGGL(apt_mfma_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, (hipStream_t)stream, (float*)out, iters);
+    hipLaunchKernelGGL(apt_mfma_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, (hipStream_t)stream, (float*)out, iters,
+                       random_operands);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 

@@ -23,6 +23,10 @@ enum {
     APT_PW_WORDS = 15,      // total words of the blob
     APT_PW_QUEUE0 = 16,     // 9 words: start of each hidden-kind queue (in items), then the end
     APT_PW_KV_TICKET = 25,  // device copy only: next KV-kind item to hand out (0 between launches)
+    APT_PW_D_MODEL = 26,    // the shape the plan was made for
+    APT_PW_BLOCK_SIZE = 27,
+    APT_PW_MAX_BLOCKS = 28,
+    APT_PW_DTYPE = 29,
     APT_PW_HEADER = 32
 };
 #define APT_N_QUEUES 8

@@ -1019,7 +1019,9 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     if (pw[APT_PW_MAGIC] != APT_PLAN_MAGIC) return APT_EINVAL;
     // the plan must have been made for this shape
     if (pw[APT_PW_HEADS] != rs.s.n_heads || pw[APT_PW_HEAD_DIM] != rs.s.head_dim || pw[APT_PW_HCHUNK] != rs.s.hidden_chunk ||
-        pw[APT_PW_KCHUNK] != rs.s.kv_chunk || pw[APT_PW_HIMPL] != rs.s.hidden_impl)
+        pw[APT_PW_KCHUNK] != rs.s.kv_chunk || pw[APT_PW_HIMPL] != rs.s.hidden_impl || pw[APT_PW_D_MODEL] != rs.s.d_model ||
+        pw[APT_PW_BLOCK_SIZE] != rs.s.block_size || pw[APT_PW_MAX_BLOCKS] != rs.s.max_blocks_per_req ||
+        pw[APT_PW_DTYPE] != rs.s.dtype)
         return APT_ESHAPE;
     const int n_items = pw[APT_PW_NITEMS], n_hidden = pw[APT_PW_NHIDDEN];
     const int B = pw[APT_PW_BATCH];

@@ -125,6 +125,10 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
     w[APT_PW_HTOK_HI] = (int32_t)(htok >> 32);
     w[APT_PW_HEAD_DIM] = rs.s.head_dim;
     w[APT_PW_WORDS] = (int32_t)words;
+    w[APT_PW_D_MODEL] = rs.s.d_model;
+    w[APT_PW_BLOCK_SIZE] = rs.s.block_size;
+    w[APT_PW_MAX_BLOCKS] = rs.s.max_blocks_per_req;
+    w[APT_PW_DTYPE] = rs.s.dtype;
 
     int32_t* split_count = w + APT_PW_HEADER;
     int32_t* ws_offset = split_count + B;

@@ -126,10 +126,10 @@ def test_attention_call_rejects_bad_arguments_before_any_launch():
         ab.apt_hybrid_decode_attn(shape, buf, None, None, None, None, None, None, None, None, None, None, None,
                                   None, None, 0)
     assert e.value.status == ab.APT_EINVAL
-    other = _shape(kv_chunk=256)
-    with pytest.raises(ab.AptError) as e:
-        ab.apt_hybrid_decode_attn(other, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 1 << 30)
-    assert e.value.status == ab.APT_ESHAPE
+    for other in (_shape(kv_chunk=256), _shape(max_blocks_per_req=64), _shape(dtype="bf16"), _shape(block_size=32)):
+        with pytest.raises(ab.AptError) as e:
+            ab.apt_hybrid_decode_attn(other, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 1 << 30)
+        assert e.value.status == ab.APT_ESHAPE
     with pytest.raises(ab.AptError) as e:
         ab.apt_hybrid_decode_attn(shape, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 8)
     assert e.value.status == ab.APT_EWORKSPACE

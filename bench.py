@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
+PEAK_VALU_F32_TFLOPS = 157.3          # 256 CUs x 2.4 GHz x 256 flops per clock (packed fp32)
 
 
 class HipEvents:
@@ -79,6 +80,9 @@ def main():
     ap.add_argument("--config", default="opt13b")
     ap.add_argument("--hidden-ratio", type=float, default=None)
     ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--hidden-impl", choices=["auto", "valu", "mfma", "absorbed"], default="auto",
+                    help="hidden-kind kernel; 'absorbed' is the re-associated form without K/V projection (its "
+                         "roofline entry is priced on its own work, never against the MFMA target)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pairs-per-thread", type=int, default=8)
     ap.add_argument("--sweep", action="store_true",
@@ -103,11 +107,12 @@ def main():
     t_gen = time.time()
     batch = wl.make_batch(cfg)
     nl = cfg.n_layers
-    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk)
+    himpl = {"auto": 0, "valu": 1, "mfma": 2, "absorbed": 3}[args.hidden_impl]
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=himpl)
     layer, dls = None, []
     for li in range(nl):                      # every layer of the step is resident in HBM
         layer = wl.make_layer(batch, layer=li, workers=min(16, os.cpu_count() or 8))
-        dls.append(rn.upload(layer, keep_raw_weights=(nl == 1)))
+        dls.append(rn.upload(layer, keep_raw_weights=(nl == 1 or himpl == 3)))
     t_gen = time.time() - t_gen
     dl = dls[-1]                              # `layer` is its host copy (cpu_baseline / parity sample)
     torch.cuda.synchronize()
@@ -144,7 +149,21 @@ def main():
     t_mfma = flops / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)
     t_hbm = (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
     wkey = f"{cfg.name}@{cfg.hidden_ratio:g}"
-    if t_mfma >= t_hbm:
+    if rn.info.hidden_impl == 3 and hidden_tokens > 0:
+        # absorbed form: per hidden token and head one d_model-long dot product and one d_model-long
+        # weighted row update in fp32 on the vector ALUs; the hidden rows are read twice
+        flops = 4.0 * d * cfg.n_heads * hidden_tokens
+        hid_bytes = 2.0 * d * e * hidden_tokens
+        t_alu, t_hbm = flops / (PEAK_VALU_F32_TFLOPS * 1e12), (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
+        if t_alu >= t_hbm:
+            ach = flops / (kern_avg_ms * 1e-3) / 1e12
+            roof = {"bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": None}
+        else:
+            ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
+            roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": ach / PEAK_HBM_GBS, "traffic": None}
+    elif t_mfma >= t_hbm:
         ach = flops / (kern_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
                 "frac": ach / PEAK_MFMA_TFLOPS[cfg.dtype], "traffic": read_traffic(wkey)}
@@ -153,7 +172,10 @@ def main():
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey)}
     mfma_items = rn.info.n_hidden_items > 0 and rn.info.hidden_impl == 2
-    roof.update({"kernel": "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel", "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
+    kname = "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel"
+    if rn.info.hidden_impl == 3 and hidden_tokens > 0:
+        kname = "apt_absorb_{q,score,stats,pv,out}_kernel + apt_items_kernel (one event pair around all six)"
+    roof.update({"kernel": kname, "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
                  "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
 
     result = {
@@ -167,6 +189,7 @@ def main():
                                + (f", {nl} layers per step (one plan, {nl} attention calls)" if nl > 1 else ""),
                    "layers_per_step": nl,
                    "total_tokens": total_tokens, "hidden_tokens": hidden_tokens, "kv_tokens": kv_tokens,
+                   "hidden_impl": {1: "valu", 2: "mfma", 3: "absorbed"}[int(rn.info.hidden_impl)],
                    "n_items": int(rn.info.n_items), "n_hidden_items": int(rn.info.n_hidden_items),
                    "seed": cfg.seed, "input_gen_s": round(t_gen, 2)},
         "roofline": roof,

@@ -71,7 +71,7 @@ typedef enum apt_status {
 
 enum { APT_F32 = 0, APT_F16 = 1, APT_BF16 = 2 };
 enum { APT_KIND_KV = 0, APT_KIND_HIDDEN = 1 };
-enum { APT_HIDDEN_AUTO = 0, APT_HIDDEN_VALU = 1, APT_HIDDEN_MFMA = 2 };
+enum { APT_HIDDEN_AUTO = 0, APT_HIDDEN_VALU = 1, APT_HIDDEN_MFMA = 2, APT_HIDDEN_ABSORBED = 3 };
 
 typedef struct apt_shape {
     int32_t d_model;            /* = n_heads * head_dim                                   */
@@ -84,7 +84,9 @@ typedef struct apt_shape {
     int32_t hidden_chunk;       /* tokens per hidden-kind work item; 0 = library default  */
     int32_t kv_chunk;           /* tokens per KV-kind work item; 0 = library default      */
     int32_t hidden_impl;        /* APT_HIDDEN_AUTO: MFMA kernel for 16-bit dtypes with
-                                   head_dim 128, plain-ALU kernel otherwise               */
+                                   head_dim 128, plain-ALU kernel otherwise.
+                                   APT_HIDDEN_ABSORBED (never chosen by AUTO): the same
+                                   output without projecting K and V, see below           */
     float softmax_scale;        /* multiplies <q, k>; 1/sqrt(head_dim) in Eq. 2's
                                    multi-head reading                                     */
     int32_t reserved;           /* must be 0                                              */
@@ -97,7 +99,7 @@ typedef struct apt_plan_info {
     int32_t n_partials;         /* sum over requests of their token ranges                */
     int32_t hidden_chunk;       /* resolved values                                        */
     int32_t kv_chunk;
-    int32_t hidden_impl;        /* resolved: APT_HIDDEN_VALU or APT_HIDDEN_MFMA           */
+    int32_t hidden_impl;        /* resolved: APT_HIDDEN_VALU, _MFMA or _ABSORBED          */
     int32_t reserved;
     int64_t total_tokens;
     int64_t hidden_tokens;
@@ -126,7 +128,9 @@ int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
  *   plan_host       caller's buffer of plan_bytes bytes (see apt_plan_max_bytes); filled
  *                   with a self-contained blob of int32 words:
  *                     [0..15] header, [16..24] queue_offset, [32..32+B) split_count,
- *                     then ws_offset[B], then (padded to a multiple of 4 words)
+ *                     then ws_offset[B] and six more per-request arrays of B words (cache
+ *                     kind, length; index, first token and first range among the hidden-kind
+ *                     requests; the list of hidden-kind requests), then (padded to a multiple of 4 words)
  *                     items[n_items][4] = (request, head, t0, t1)
  *   info            optional, receives the counts and the workspace size
  * The rule: a request of n tokens is cut into ceil(n/C) ranges [s*C, min(n,(s+1)*C)),
@@ -136,7 +140,9 @@ int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
  * holding the heads with h % 8 == x (queue_offset[x] = its first item, queue_offset[8] = the
  * number of hidden-kind items), in a queue first the full ranges by request, range, head, then
  * the shorter last ranges by decreasing length (ties by request, head); then the KV kind by
- * decreasing range length (ties by request, range, head).  The order only steers which
+ * decreasing range length (ties by request, range, head).  With APT_HIDDEN_ABSORBED a hidden-kind
+ * item covers all heads of its range: one item (request, 0, t0, t1) per range, all in queue 0, by
+ * request and range.  The order only steers which
  * workgroup takes which item (cache locality, balance); every item is independent.
  * Integer-only; the same inputs always give the same bytes.
  * Errors: APT_EINVAL (null, B < 1, length < 1, unknown kind), APT_ERANGE (length
@@ -200,6 +206,18 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
                            const void* W_K, const void* W_V, const void* W_packed,
                            const void* b_K, const void* b_V, const int32_t* block_tables,
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * APT_HIDDEN_ABSORBED.  Not in the paper: an exact re-association of Eq. 1-3 for hidden-kind
+ * requests.  With qt = W_K[:, h] q (a d_model vector per request and head) the score of token j is
+ * scale * (<x_j, qt> + <q, b_K[h]>), and because the softmax weights a_j sum to one,
+ * out = (sum_j a_j x_j) W_V[:, h] + b_V[h].  The cached hidden rows are then read twice (scores,
+ * weighted sum) like the K and V rows of a KV-kind request, and the two projections shrink to one
+ * matrix-vector product per request and head.  Work per hidden token: 4 * d_model * n_heads flops
+ * instead of 4 * d_model^2.  Results agree with the other implementations to fp32 rounding.  Needs
+ * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 40, and a larger workspace
+ * (apt_plan_info.workspace_bytes says how much); hidden_chunk must be 0 or 512.
+ */
 
 /*
  * The same step as apt_hybrid_decode_attn (Eq. 1-3 over both cache kinds); in addition

@@ -37,7 +37,10 @@ def ceil_div(a, b):
     return -(-a // b)
 
 
-def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk):
+def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk, hidden_item_per_head=True):
+    """hidden_item_per_head=False: the absorbed-weight hidden path, whose items serve all heads of a
+    range at once: one item (r, 0, t0, t1) per range of a hidden-kind request, by request and range,
+    all in queue 0."""
     B = len(ctx_lens)
     split_count, ws_offset = [], []
     run = 0
@@ -65,8 +68,14 @@ def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk):
     items = []
     queue_offset = []
     hidden = all_items(KIND_HIDDEN, hidden_chunk)
+    if not hidden_item_per_head:
+        hidden = [it for it in hidden if it[1] == 0]
     for x in range(N_QUEUES):
         queue_offset.append(len(items))
+        if not hidden_item_per_head:
+            if x == 0:
+                items += sorted(hidden, key=lambda it: (it[0], it[2]))
+            continue
         mine = [it for it in hidden if it[1] % N_QUEUES == x]
         full = [it for it in mine if it[3] - it[2] == hidden_chunk]
         tails = [it for it in mine if it[3] - it[2] != hidden_chunk]

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libapt_hybrid.so")
 
 APT_F32, APT_F16, APT_BF16 = 0, 1, 2
 APT_KIND_KV, APT_KIND_HIDDEN = 0, 1
-APT_HIDDEN_AUTO, APT_HIDDEN_VALU, APT_HIDDEN_MFMA = 0, 1, 2
+APT_HIDDEN_AUTO, APT_HIDDEN_VALU, APT_HIDDEN_MFMA, APT_HIDDEN_ABSORBED = 0, 1, 2, 3
 APT_OK, APT_EINVAL, APT_ESHAPE, APT_EDTYPE, APT_EWORKSPACE, APT_EHIP, APT_ERANGE = 0, -1, -2, -3, -4, -5, -6
 DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 

@@ -27,6 +27,7 @@ enum {
     APT_PW_BLOCK_SIZE = 27,
     APT_PW_MAX_BLOCKS = 28,
     APT_PW_DTYPE = 29,
+    APT_PW_NHIDREQ = 30,    // number of hidden-kind requests
     APT_PW_HEADER = 32
 };
 #define APT_N_QUEUES 8
@@ -38,6 +39,22 @@ enum {
 #define APT_DEFAULT_VALU_HIDDEN_CHUNK 32
 #define APT_MAX_VALU_HIDDEN_CHUNK 64
 #define APT_KV_MAX_PAGES_PER_WAVE 64
+#define APT_ABSORBED_HEAD_GROUPS 4       // absorbed-weight kernels: threads of a workgroup = 64 x 4 (token or column
+#define APT_ABSORBED_HEADS_PER_THREAD 10 // group, head group), 8 tokens/columns x 10 heads per thread
+#define APT_ABSORBED_CHUNK 512           // = 64 groups x 8 tokens
+
+// per-request arrays of the plan blob, each B words, starting at APT_PW_HEADER
+enum {
+    APT_PA_SPLIT_COUNT = 0,    // ranges of the request
+    APT_PA_WS_OFFSET = 1,      // its first partial
+    APT_PA_KIND = 2,           // APT_KIND_*
+    APT_PA_CTX_LEN = 3,        // cached tokens
+    APT_PA_HID_INDEX = 4,      // hidden-kind requests only (-1 otherwise): index among them,
+    APT_PA_HID_TOK_OFF = 5,    //   tokens of the hidden-kind requests before it,
+    APT_PA_HID_CHUNK_OFF = 6,  //   ranges of the hidden-kind requests before it
+    APT_PA_HID_REQ = 7,        // entry i: the request that is hidden-kind request i (-1 past their number)
+    APT_PA_COUNT = 8
+};
 
 struct apt_resolved {
     apt_shape s;        // chunks and hidden_impl filled in
@@ -47,7 +64,34 @@ struct apt_resolved {
 // Validates a shape and fills the defaults.  Returns an apt_status.
 int apt_resolve(const apt_shape* in, apt_resolved* out);
 
-static inline uint64_t apt_ws_bytes(int64_t n_partials, int H, int hd) {
-    // per slot: head_dim floats of un-normalised output + (m, l)
-    return (uint64_t)n_partials * (uint64_t)H * (uint64_t)(hd + 2) * 4u;
+static inline uint64_t apt_align256(uint64_t v) { return (v + 255u) & ~(uint64_t)255u; }
+
+// Workspace sections.  Always: the partials (per slot head_dim floats of un-normalised output, then (m, l)).
+// Absorbed-weight hidden path in addition (fp32), with KS = ceil(d / 512) slices of d_model: absorbed queries
+// QT [n_hid_req][H][d], score offsets CB [n_hid_req][H], score partials S [KS][H][hidden_tokens] (slice 0 then
+// holds the scores), statistics ML [n_hid_req][H] (m, l), the partial weighted sums YP [n_hidden_chunks][H][d]
+// and the output partials OP [KS][n_hid_req][H][hd].
+struct apt_ws_layout {
+    uint64_t acc, ml, qt, cb, s, stat, yp, op, total;
+};
+static inline apt_ws_layout apt_ws_sections(int64_t n_partials, int H, int hd, int himpl, int64_t n_hid_req,
+                                            int64_t hidden_tokens, int64_t n_hid_chunks, int d) {
+    apt_ws_layout L;
+    const uint64_t slots = (uint64_t)n_partials * (uint64_t)H;
+    L.acc = 0;
+    L.ml = slots * (uint64_t)hd * 4u;
+    uint64_t end = L.ml + slots * 8u;
+    L.qt = L.cb = L.s = L.stat = L.yp = L.op = 0;
+    if (himpl == APT_HIDDEN_ABSORBED) {
+        const uint64_t ks = (uint64_t)(d + APT_ABSORBED_CHUNK - 1) / APT_ABSORBED_CHUNK;
+        L.qt = apt_align256(end);
+        L.cb = apt_align256(L.qt + (uint64_t)n_hid_req * H * d * 4u);
+        L.s = apt_align256(L.cb + (uint64_t)n_hid_req * H * 4u);
+        L.stat = apt_align256(L.s + ks * (uint64_t)hidden_tokens * H * 4u);
+        L.yp = apt_align256(L.stat + (uint64_t)n_hid_req * H * 8u);
+        L.op = apt_align256(L.yp + (uint64_t)n_hid_chunks * H * d * 4u);
+        end = L.op + ks * (uint64_t)n_hid_req * H * hd * 4u;
+    }
+    L.total = end;
+    return L;
 }

@@ -49,6 +49,16 @@ struct ItemParams {
     int32_t B, H, d, bs, log2_bs, max_blocks;
     int32_t n_items, n_hidden_items, hidden_chunk, kv_chunk, items_off;
     float scale_log2e;
+    int32_t item_base;            // one-workgroup-per-item launch: first item of the grid
+    // absorbed-weight hidden path: workspace sections (fp32)
+    float* ab_qt;                 // [n_hid_req][H][d]
+    float* ab_cb;                 // [n_hid_req][H]
+    float* ab_s;                  // [KS][H][ab_tokens] partial scores over d_model slices; slice 0 ends as the scores
+    float2* ab_ml;                // [n_hid_req][H]
+    float* ab_yp;                 // [n_hidden_items][H][d]
+    float* ab_op;                 // [KS][n_hid_req][H][HD]
+    int64_t ab_tokens;            // cached tokens of all hidden-kind requests
+    int32_t n_hid_req;
     int32_t dbg;                  // experiment switches (0 in production)
     long long* dbg_buf;           // experiment output: per-workgroup clock stamps (null in production)
 };
@@ -735,7 +745,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 template <int DT, int HD, int HIMPL>
 __global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
     extern __shared__ __align__(16) char lds[];
-    const int item = blockIdx.x;
+    const int item = blockIdx.x + p.item_base;
     if (item >= p.n_items) return;
     const int4 it = ((const int4*)(p.plan + p.items_off))[item];
     if (item < p.n_hidden_items) {
@@ -750,15 +760,18 @@ __global__ __launch_bounds__(kThreads) void apt_items_kernel(ItemParams p) {
 // ---------------------------------------------------------------------------------
 template <int ODT>
 __global__ __launch_bounds__(kThreads) void apt_merge_kernel(const int32_t* plan, const float* ws_acc, const float2* ws_ml,
-                                                             char* out, int B, int H, int HD, int32_t* kv_ticket) {
+                                                             char* out, int B, int H, int HD, int32_t* kv_ticket,
+                                                             int skip_hidden) {
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (gid == 0) *kv_ticket = 0;           // the item kernel of this call is done: ready for the next call
     if (gid >= (int64_t)B * H * HD) return;
     const int c = (int)(gid % HD);
     const int64_t pair = gid / HD;
     const int h = (int)(pair % H), r = (int)(pair / H);
-    const int32_t* split_count = plan + APT_PW_HEADER;
-    const int32_t* ws_offset = split_count + B;
+    const int32_t* split_count = plan + APT_PW_HEADER + APT_PA_SPLIT_COUNT * B;
+    const int32_t* ws_offset = plan + APT_PW_HEADER + APT_PA_WS_OFFSET * B;
+    // absorbed-weight path: the outputs of hidden-kind requests are already written
+    if (skip_hidden && plan[APT_PW_HEADER + APT_PA_KIND * B + r] == APT_KIND_HIDDEN) return;
     const int ns = split_count[r];
     const int64_t base = (int64_t)ws_offset[r] * H + h;
     float M = kSentinel;
@@ -892,9 +905,11 @@ int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
             return APT_EHIP;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(p.n_items), dim3(kThreads), lds_bytes, st, p);
+    hipLaunchKernelGGL(kern, dim3(p.n_items - p.item_base), dim3(kThreads), lds_bytes, st, p);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
+
+#include "apt_absorbed.inc"
 
 // persistent launch: one workgroup per compute unit, a multiple of 8
 template <int DT, int EXP>
@@ -914,12 +929,19 @@ int launch_mfma(const ItemParams& p, hipStream_t st) {
 }
 
 template <int DT, int HD>
-int launch_items_impl(const ItemParams& p, int himpl, hipStream_t st) {
+int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtype, hipStream_t st) {
     constexpr int EB = Elt<DT>::bytes;
     constexpr int LPR = HD * EB / 16;
     constexpr int G = 4 * (64 / LPR);
     const size_t kv_lds = (size_t)(2 * G + G * HD) * 4;
+    ItemParams p = p_in;
     if (p.n_hidden_items == 0) return launch_items<DT, HD, 0>(p, kv_lds, st);
+    if (himpl == APT_HIDDEN_ABSORBED) {
+        const int rc = launch_absorbed<DT>(p, out, out_dtype, HD, st);
+        if (rc || p.n_hidden_items == p.n_items) return rc;
+        p.item_base = p.n_hidden_items;          // the KV-kind items, one workgroup each
+        return launch_items<DT, HD, 0>(p, kv_lds, st);
+    }
     if (himpl == APT_HIDDEN_VALU) {
         size_t v = (size_t)(2 * p.hidden_chunk * (HD + 1) + 64 + 2) * 4;
         return launch_items<DT, HD, 1>(p, v > kv_lds ? v : kv_lds, st);
@@ -1025,14 +1047,16 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
         return APT_ESHAPE;
     const int n_items = pw[APT_PW_NITEMS], n_hidden = pw[APT_PW_NHIDDEN];
     const int B = pw[APT_PW_BATCH];
-    const uint64_t need = apt_ws_bytes(pw[APT_PW_NPARTIALS], rs.s.n_heads, rs.s.head_dim);
-    if (workspace_bytes < need) return APT_EWORKSPACE;
+    const int64_t hidden_tokens = ((int64_t)pw[APT_PW_HTOK_HI] << 32) | (uint32_t)pw[APT_PW_HTOK_LO];
+    const apt_ws_layout L = apt_ws_sections(pw[APT_PW_NPARTIALS], rs.s.n_heads, rs.s.head_dim, rs.s.hidden_impl,
+                                            pw[APT_PW_NHIDREQ], hidden_tokens, n_hidden, rs.s.d_model);
+    if (workspace_bytes < L.total) return APT_EWORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return APT_EINVAL;
     if (n_hidden < n_items && (!k_pages || !v_pages)) return APT_EINVAL;
     if (n_hidden > 0) {
         if (!hidden_pages || !b_K || !b_V) return APT_EINVAL;
         if (rs.s.hidden_impl == APT_HIDDEN_MFMA && !W_packed) return APT_EINVAL;
-        if (rs.s.hidden_impl == APT_HIDDEN_VALU && (!W_K || !W_V)) return APT_EINVAL;
+        if (rs.s.hidden_impl != APT_HIDDEN_MFMA && (!W_K || !W_V)) return APT_EINVAL;
     }
     int log2_bs = 0;
     while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
@@ -1050,9 +1074,18 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     p.b_K = (const char*)b_K;
     p.b_V = (const char*)b_V;
     p.block_tables = block_tables;
-    const int64_t n_slots = (int64_t)pw[APT_PW_NPARTIALS] * rs.s.n_heads;
-    p.ws_acc = (float*)workspace;
-    p.ws_ml = (float2*)((float*)workspace + n_slots * rs.s.head_dim);
+    char* const ws = (char*)workspace;
+    p.ws_acc = (float*)(ws + L.acc);
+    p.ws_ml = (float2*)(ws + L.ml);
+    p.ab_qt = (float*)(ws + L.qt);
+    p.ab_cb = (float*)(ws + L.cb);
+    p.ab_s = (float*)(ws + L.s);
+    p.ab_ml = (float2*)(ws + L.stat);
+    p.ab_yp = (float*)(ws + L.yp);
+    p.ab_op = (float*)(ws + L.op);
+    p.ab_tokens = hidden_tokens;
+    p.n_hid_req = pw[APT_PW_NHIDREQ];
+    p.item_base = 0;
     p.B = B; p.H = rs.s.n_heads; p.d = rs.s.d_model; p.bs = rs.s.block_size; p.log2_bs = log2_bs;
     p.max_blocks = rs.s.max_blocks_per_req;
     p.n_items = n_items; p.n_hidden_items = n_hidden;
@@ -1068,23 +1101,24 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
 
     const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;
     if (ev_begin && hipEventRecord((hipEvent_t)ev_begin, st) != hipSuccess) return APT_EHIP;
-    if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, st);
-    else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, st);
-    else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, st);
-    else if (dt == APT_F16 && hd == 128) rc = launch_items_impl<1, 128>(p, hi, st);
-    else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, st);
-    else rc = launch_items_impl<2, 128>(p, hi, st);
+    if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
+    else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
+    else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
+    else if (dt == APT_F16 && hd == 128) rc = launch_items_impl<1, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
+    else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
+    else rc = launch_items_impl<2, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
     if (rc) return rc;
     if (ev_end && hipEventRecord((hipEvent_t)ev_end, st) != hipSuccess) return APT_EHIP;
 
+    const int skip_hidden = hi == APT_HIDDEN_ABSORBED;
     const int64_t total = (int64_t)B * rs.s.n_heads * hd;
     const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
     if (rs.s.out_dtype == APT_F32)
-        hipLaunchKernelGGL(apt_merge_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
+        hipLaunchKernelGGL(apt_merge_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket, skip_hidden);
     else if (rs.s.out_dtype == APT_F16)
-        hipLaunchKernelGGL(apt_merge_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
+        hipLaunchKernelGGL(apt_merge_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket, skip_hidden);
     else
-        hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket);
+        hipLaunchKernelGGL(apt_merge_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, p.plan, p.ws_acc, p.ws_ml, (char*)out, B, rs.s.n_heads, hd, p.kv_ticket, skip_hidden);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 

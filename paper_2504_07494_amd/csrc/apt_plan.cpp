@@ -43,6 +43,10 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
         if (!mfma_ok) return APT_ESHAPE;
         if (s.hidden_chunk == 0) s.hidden_chunk = APT_MFMA_HIDDEN_CHUNK;
         if (s.hidden_chunk != APT_MFMA_HIDDEN_CHUNK) return APT_ESHAPE;
+    } else if (s.hidden_impl == APT_HIDDEN_ABSORBED) {
+        if (s.d_model % 32 != 0 || s.n_heads > APT_ABSORBED_HEAD_GROUPS * APT_ABSORBED_HEADS_PER_THREAD) return APT_ESHAPE;
+        if (s.hidden_chunk == 0) s.hidden_chunk = APT_ABSORBED_CHUNK;
+        if (s.hidden_chunk != APT_ABSORBED_CHUNK) return APT_ESHAPE;
     } else if (s.hidden_impl == APT_HIDDEN_VALU) {
         if (s.hidden_chunk == 0) s.hidden_chunk = APT_DEFAULT_VALU_HIDDEN_CHUNK;
         if (s.hidden_chunk < 1 || s.hidden_chunk > APT_MAX_VALU_HIDDEN_CHUNK) return APT_ESHAPE;
@@ -63,7 +67,7 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
 static int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 static size_t plan_words(int B, int64_t n_items) {
-    size_t w = APT_PW_HEADER + 2 * (size_t)B;
+    size_t w = APT_PW_HEADER + APT_PA_COUNT * (size_t)B;
     w = (w + 3) & ~(size_t)3;
     return w + 4 * (size_t)n_items;
 }
@@ -89,7 +93,8 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
     const int64_t max_len = (int64_t)rs.s.max_blocks_per_req * rs.s.block_size;
 
     // pass 1: validate and count
-    int64_t n_partials = 0, n_hidden_items = 0, n_items = 0, tok = 0, htok = 0;
+    const bool absorbed = rs.s.hidden_impl == APT_HIDDEN_ABSORBED;
+    int64_t n_partials = 0, n_hidden_items = 0, n_items = 0, tok = 0, htok = 0, n_hid_req = 0;
     for (int r = 0; r < B; ++r) {
         const int n = ctx_lens[r];
         if (n < 1) return APT_EINVAL;
@@ -97,12 +102,13 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
         if (cache_kind[r] != APT_KIND_KV && cache_kind[r] != APT_KIND_HIDDEN) return APT_EINVAL;
         const bool hid = cache_kind[r] == APT_KIND_HIDDEN;
         const int64_t sp = ceil_div64(n, hid ? rs.s.hidden_chunk : rs.s.kv_chunk);
+        const int64_t per_range = (hid && absorbed) ? 1 : H;      // absorbed: one item serves all heads
         n_partials += sp;
-        n_items += sp * H;
-        if (hid) { n_hidden_items += sp * H; htok += n; }
+        n_items += sp * per_range;
+        if (hid) { n_hidden_items += sp * per_range; htok += n; ++n_hid_req; }
         tok += n;
     }
-    if (n_items > 0x7fffffff || n_partials * (int64_t)H > 0x7fffffff) return APT_ERANGE;
+    if (n_items > 0x7fffffff || n_partials * (int64_t)H > 0x7fffffff || htok > 0x7fffffff) return APT_ERANGE;
     const size_t words = plan_words(B, n_items);
     if (plan_bytes < words * 4) return APT_EWORKSPACE;
 
@@ -129,15 +135,30 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
     w[APT_PW_BLOCK_SIZE] = rs.s.block_size;
     w[APT_PW_MAX_BLOCKS] = rs.s.max_blocks_per_req;
     w[APT_PW_DTYPE] = rs.s.dtype;
+    w[APT_PW_NHIDREQ] = (int32_t)n_hid_req;
 
-    int32_t* split_count = w + APT_PW_HEADER;
-    int32_t* ws_offset = split_count + B;
-    int32_t run = 0;
+    int32_t* split_count = w + APT_PW_HEADER + APT_PA_SPLIT_COUNT * B;
+    int32_t* ws_offset = w + APT_PW_HEADER + APT_PA_WS_OFFSET * B;
+    int32_t* kind = w + APT_PW_HEADER + APT_PA_KIND * B;
+    int32_t* hid_index = w + APT_PW_HEADER + APT_PA_HID_INDEX * B;
+    int32_t* hid_tok_off = w + APT_PW_HEADER + APT_PA_HID_TOK_OFF * B;
+    int32_t* hid_chunk_off = w + APT_PW_HEADER + APT_PA_HID_CHUNK_OFF * B;
+    int32_t* hid_req = w + APT_PW_HEADER + APT_PA_HID_REQ * B;
+    int32_t* ctx_len = w + APT_PW_HEADER + APT_PA_CTX_LEN * B;
+    for (int r = 0; r < B; ++r) hid_req[r] = -1;
+    int32_t run = 0, hi = 0, ht = 0, hc = 0;
     for (int r = 0; r < B; ++r) {
         const bool hid = cache_kind[r] == APT_KIND_HIDDEN;
         split_count[r] = (int32_t)ceil_div64(ctx_lens[r], hid ? rs.s.hidden_chunk : rs.s.kv_chunk);
         ws_offset[r] = run;
         run += split_count[r];
+        kind[r] = cache_kind[r];
+        ctx_len[r] = ctx_lens[r];
+        if (hid) hid_req[hi] = r;
+        hid_index[r] = hid ? hi : -1;
+        hid_tok_off[r] = hid ? ht : -1;
+        hid_chunk_off[r] = hid ? hc : -1;
+        if (hid) { ++hi; ht += ctx_lens[r]; hc += split_count[r]; }
     }
     // pass 2: items.  Hidden kind first, in APT_N_QUEUES queues by head % 8; in a queue the
     // full ranges come first (request, range, head order), then the last, shorter ranges by
@@ -170,7 +191,19 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
     };
     for (int x = 0; x < APT_N_QUEUES; ++x) {
         w[APT_PW_QUEUE0 + x] = (int32_t)((it - it0) / 4);
-        emit_kind(APT_KIND_HIDDEN, rs.s.hidden_chunk, x, APT_N_QUEUES);
+        if (!absorbed) {
+            emit_kind(APT_KIND_HIDDEN, rs.s.hidden_chunk, x, APT_N_QUEUES);
+        } else if (x == 0) {           // one item per range, by request and range, all in queue 0
+            for (int r = 0; r < B; ++r) {
+                if (cache_kind[r] != APT_KIND_HIDDEN) continue;
+                for (int sp = 0; sp < split_count[r]; ++sp) {
+                    const int t0 = sp * rs.s.hidden_chunk;
+                    it[0] = r; it[1] = 0; it[2] = t0;
+                    it[3] = t0 + rs.s.hidden_chunk < ctx_lens[r] ? t0 + rs.s.hidden_chunk : ctx_lens[r];
+                    it += 4;
+                }
+            }
+        }
     }
     w[APT_PW_QUEUE0 + APT_N_QUEUES] = (int32_t)((it - it0) / 4);
     emit_kind(APT_KIND_KV, rs.s.kv_chunk, 0, 1);
@@ -193,7 +226,8 @@ extern "C" int apt_plan_get_info(const void* plan_host, apt_plan_info* info) {
     info->total_tokens = ((int64_t)w[APT_PW_TOK_HI] << 32) | (uint32_t)w[APT_PW_TOK_LO];
     info->hidden_tokens = ((int64_t)w[APT_PW_HTOK_HI] << 32) | (uint32_t)w[APT_PW_HTOK_LO];
     info->plan_bytes = (uint64_t)(uint32_t)w[APT_PW_WORDS] * 4u;
-    info->workspace_bytes = apt_ws_bytes(w[APT_PW_NPARTIALS], w[APT_PW_HEADS], w[APT_PW_HEAD_DIM]);
+    info->workspace_bytes = apt_ws_sections(w[APT_PW_NPARTIALS], w[APT_PW_HEADS], w[APT_PW_HEAD_DIM], w[APT_PW_HIMPL],
+                                            w[APT_PW_NHIDREQ], info->hidden_tokens, w[APT_PW_NHIDDEN], w[APT_PW_D_MODEL]).total;
     return APT_OK;
 }
 

@@ -70,6 +70,41 @@ def test_plan_with_explicit_chunks_and_small_heads():
     assert ab.decode_plan(buf) == po.plan(lens, kinds, 4, 8, 32)
 
 
+def test_absorbed_plan_has_one_hidden_item_per_range_and_the_request_maps():
+    g = np.random.default_rng(11)
+    B = 37
+    lens = g.integers(1, 2049, size=B)
+    kinds = (g.random(B) < 0.5).astype(np.uint8)
+    shape = _shape(hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    buf, info = _plan(shape, lens, kinds)
+    assert info.hidden_impl == ab.APT_HIDDEN_ABSORBED and info.hidden_chunk == 512
+    want = po.plan(lens, kinds, 40, 512, info.kv_chunk, hidden_item_per_head=False)
+    assert ab.decode_plan(buf) == want
+    # per-request maps of the hidden-kind requests, from their plain definitions
+    w = buf.view(np.int32)
+    arr = lambda i: w[32 + i * B:32 + (i + 1) * B].tolist()
+    hid = [r for r in range(B) if kinds[r] == 1]
+    assert arr(2) == kinds.tolist() and arr(3) == lens.tolist()
+    assert arr(7) == hid + [-1] * (B - len(hid))
+    tok = chunk = 0
+    for i, r in enumerate(hid):
+        assert (arr(4)[r], arr(5)[r], arr(6)[r]) == (i, tok, chunk)
+        tok += int(lens[r])
+        chunk += -(-int(lens[r]) // 512)
+    assert all(arr(4)[r] == -1 for r in range(B) if kinds[r] == 0)
+    # workspace: partials + QT + CB + S slices + (m, l) + YP + output partials, each section 256-byte aligned
+    al = lambda v: (v + 255) // 256 * 256
+    H, d, nh = 40, 5120, len(hid)
+    end = want["n_partials"] * H * (128 + 2) * 4
+    ks = d // 512
+    for sec in (nh * H * d * 4, nh * H * 4, ks * tok * H * 4, nh * H * 8, chunk * H * d * 4):
+        end = al(end) + sec
+    assert info.workspace_bytes == al(end) + ks * nh * H * 128 * 4
+    for bad in (dict(n_heads=41, d_model=41 * 128), dict(hidden_chunk=256)):
+        with pytest.raises(ab.AptError):
+            _plan(_shape(hidden_impl=ab.APT_HIDDEN_ABSORBED, **bad), lens, kinds)
+
+
 def test_plan_rejects_bad_arguments():
     shape = _shape()
     buf = np.zeros(1 << 16, dtype=np.int32)

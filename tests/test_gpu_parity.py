@@ -85,6 +85,38 @@ def test_valu_hidden_and_kv_layout_variants(oracle, dtype, hd, H, bs):
     _check(got, _full(oracle, batch, layer), f"valu-{dtype}-hd{hd}-bs{bs}", 2e-4, 2e-3)
 
 
+@pytest.mark.parametrize("dtype,hd,H,bs", [("f16", 128, 4, 16), ("bf16", 128, 4, 16), ("f32", 128, 2, 16),
+                                            ("f16", 64, 6, 8), ("f32", 64, 5, 4)])
+def test_absorbed_weight_hidden_path(oracle, dtype, hd, H, bs):
+    # same step, hidden-kind requests through the re-associated form (no K/V projection)
+    print(f"[case] absorbed {dtype} hd={hd} H={H} bs={bs}", flush=True)
+    cfg = wl.small_config(name="absorbed", dtype=dtype, d_model=hd * H, n_heads=H, head_dim=hd, block_size=bs,
+                          batch=8, len_lo=1, len_hi=1300, hidden_ratio=0.5)
+    lens = np.array([1300, 257, 1, 512, 513, 256, 33, 1024], dtype=np.int32)
+    kinds = np.array([HID, HID, HID, KV, KV, HID, KV, HID], dtype=np.uint8)
+    batch = wl.make_batch(cfg, lens, kinds)
+    layer = wl.make_layer(batch)
+    rn, got = _run(batch, layer, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    assert rn.info.hidden_impl == ab.APT_HIDDEN_ABSORBED
+    _check(got, _full(oracle, batch, layer), f"absorbed-{dtype}-hd{hd}", 2e-4, 2e-3)
+
+
+def test_absorbed_path_many_requests_pure_hidden_and_sixteen_bit_output(oracle):
+    # more hidden-kind requests than one pass of the projection kernels holds (16), no KV-kind item
+    print("[case] absorbed pure hidden, 19 requests", flush=True)
+    cfg = wl.small_config(name="absorbed19", dtype="f16", d_model=512, n_heads=4, head_dim=128, block_size=16,
+                          batch=19, len_lo=1, len_hi=600, hidden_ratio=1.0)
+    batch = wl.make_batch(cfg)
+    layer = wl.make_layer(batch)
+    rn, got = _run(batch, layer, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    _check(got, _full(oracle, batch, layer), "absorbed-19", 2e-4, 2e-3)
+    _, got16 = _run(batch, layer, hidden_impl=ab.APT_HIDDEN_ABSORBED, out_dtype="f16")
+    ref = torch.from_numpy(got.astype(np.float32)).to(torch.float16)
+    assert np.array_equal(got16, ref.float().numpy().astype(np.float64))
+    _, mf = _run(batch, layer)
+    assert np.max(np.abs(got - mf)) < 1e-4
+
+
 def test_mfma_and_valu_hidden_kernels_agree(oracle):
     print("[case] mfma vs valu", flush=True)
     cfg = wl.small_config(name="agree", dtype="f16", **{**MID, "batch": 3})

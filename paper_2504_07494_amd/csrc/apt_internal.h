@@ -68,29 +68,33 @@ static inline uint64_t apt_align256(uint64_t v) { return (v + 255u) & ~(uint64_t
 
 // Workspace sections.  Always: the partials (per slot head_dim floats of un-normalised output, then (m, l)).
 // Absorbed-weight hidden path in addition (fp32), with KS = ceil(d / 512) slices of d_model: absorbed queries
-// QT [n_hid_req][H][d], score offsets CB [n_hid_req][H], score partials S [KS][H][hidden_tokens] (slice 0 then
+// QT [n_hid_req][H][d] (16-bit inputs: [n_hid_req][d / 32][parts * 64][32] 16-bit parts), score offsets CB [n_hid_req][H], score partials S [KS][H][hidden_tokens] (slice 0 then
 // holds the scores), statistics ML [n_hid_req][H] (m, l), the partial weighted sums YP [n_hidden_chunks][H][d]
-// and the output partials OP [KS][n_hid_req][H][hd].
+// the output partials OP [KS][n_hid_req][H][hd], and (16-bit inputs) the softmax weights PP as 16-bit parts.
 struct apt_ws_layout {
-    uint64_t acc, ml, qt, cb, s, stat, yp, op, total;
+    uint64_t acc, ml, qt, cb, s, stat, yp, op, pp, total;
 };
 static inline apt_ws_layout apt_ws_sections(int64_t n_partials, int H, int hd, int himpl, int64_t n_hid_req,
-                                            int64_t hidden_tokens, int64_t n_hid_chunks, int d) {
+                                            int64_t hidden_tokens, int64_t n_hid_chunks, int d, int dtype) {
     apt_ws_layout L;
     const uint64_t slots = (uint64_t)n_partials * (uint64_t)H;
     L.acc = 0;
     L.ml = slots * (uint64_t)hd * 4u;
     uint64_t end = L.ml + slots * 8u;
-    L.qt = L.cb = L.s = L.stat = L.yp = L.op = 0;
+    L.qt = L.cb = L.s = L.stat = L.yp = L.op = L.pp = 0;
     if (himpl == APT_HIDDEN_ABSORBED) {
         const uint64_t ks = (uint64_t)(d + APT_ABSORBED_CHUNK - 1) / APT_ABSORBED_CHUNK;
         L.qt = apt_align256(end);
-        L.cb = apt_align256(L.qt + (uint64_t)n_hid_req * H * d * 4u);
+        // 16-bit inputs: QT is kept as 16-bit parts (2 for fp16, 3 for bf16) of 64 padded heads instead
+        const uint64_t qt_per_elem = dtype == APT_F32 ? (uint64_t)H * 4u : (dtype == APT_F16 ? 256u : 384u);
+        L.cb = apt_align256(L.qt + (uint64_t)n_hid_req * d * qt_per_elem);
         L.s = apt_align256(L.cb + (uint64_t)n_hid_req * H * 4u);
         L.stat = apt_align256(L.s + ks * (uint64_t)hidden_tokens * H * 4u);
         L.yp = apt_align256(L.stat + (uint64_t)n_hid_req * H * 8u);
         L.op = apt_align256(L.yp + (uint64_t)n_hid_chunks * H * d * 4u);
-        end = L.op + ks * (uint64_t)n_hid_req * H * hd * 4u;
+        L.pp = apt_align256(L.op + ks * (uint64_t)n_hid_req * H * hd * 4u);
+        // 16-bit inputs: the softmax weights as 16-bit parts, 16 tiles of 32 tokens per range, 64 padded heads
+        end = L.pp + (dtype == APT_F32 ? 0u : (uint64_t)n_hid_chunks * 16u * 32u * qt_per_elem);
     }
     L.total = end;
     return L;

@@ -57,6 +57,7 @@ struct ItemParams {
     float2* ab_ml;                // [n_hid_req][H]
     float* ab_yp;                 // [n_hidden_items][H][d]
     float* ab_op;                 // [KS][n_hid_req][H][HD]
+    void* ab_pp;                  // 16-bit inputs: softmax weights as 16-bit parts, [16 n_hidden_items][parts * 64][32]
     int64_t ab_tokens;            // cached tokens of all hidden-kind requests
     int32_t n_hid_req;
     int32_t dbg;                  // experiment switches (0 in production)
@@ -1049,7 +1050,7 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     const int B = pw[APT_PW_BATCH];
     const int64_t hidden_tokens = ((int64_t)pw[APT_PW_HTOK_HI] << 32) | (uint32_t)pw[APT_PW_HTOK_LO];
     const apt_ws_layout L = apt_ws_sections(pw[APT_PW_NPARTIALS], rs.s.n_heads, rs.s.head_dim, rs.s.hidden_impl,
-                                            pw[APT_PW_NHIDREQ], hidden_tokens, n_hidden, rs.s.d_model);
+                                            pw[APT_PW_NHIDREQ], hidden_tokens, n_hidden, rs.s.d_model, rs.s.dtype);
     if (workspace_bytes < L.total) return APT_EWORKSPACE;
     if (((uintptr_t)workspace & 15) != 0) return APT_EINVAL;
     if (n_hidden < n_items && (!k_pages || !v_pages)) return APT_EINVAL;
@@ -1083,6 +1084,7 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     p.ab_ml = (float2*)(ws + L.stat);
     p.ab_yp = (float*)(ws + L.yp);
     p.ab_op = (float*)(ws + L.op);
+    p.ab_pp = ws + L.pp;
     p.ab_tokens = hidden_tokens;
     p.n_hid_req = pw[APT_PW_NHIDREQ];
     p.item_base = 0;

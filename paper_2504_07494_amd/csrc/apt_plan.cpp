@@ -227,7 +227,8 @@ extern "C" int apt_plan_get_info(const void* plan_host, apt_plan_info* info) {
     info->hidden_tokens = ((int64_t)w[APT_PW_HTOK_HI] << 32) | (uint32_t)w[APT_PW_HTOK_LO];
     info->plan_bytes = (uint64_t)(uint32_t)w[APT_PW_WORDS] * 4u;
     info->workspace_bytes = apt_ws_sections(w[APT_PW_NPARTIALS], w[APT_PW_HEADS], w[APT_PW_HEAD_DIM], w[APT_PW_HIMPL],
-                                            w[APT_PW_NHIDREQ], info->hidden_tokens, w[APT_PW_NHIDDEN], w[APT_PW_D_MODEL]).total;
+                                            w[APT_PW_NHIDREQ], info->hidden_tokens, w[APT_PW_NHIDDEN], w[APT_PW_D_MODEL],
+                                            w[APT_PW_DTYPE]).total;
     return APT_OK;
 }
 

@@ -29,7 +29,6 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
-PEAK_VALU_F32_TFLOPS = 157.3          # 256 CUs x 2.4 GHz x 256 flops per clock (packed fp32)
 
 
 class HipEvents:
@@ -150,19 +149,14 @@ def main():
     t_hbm = (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
     wkey = f"{cfg.name}@{cfg.hidden_ratio:g}"
     if rn.info.hidden_impl == 3 and hidden_tokens > 0:
-        # absorbed form: per hidden token and head one d_model-long dot product and one d_model-long
-        # weighted row update in fp32 on the vector ALUs; the hidden rows are read twice
+        # absorbed form: no projection; per hidden token and head one d_model-long dot product and one
+        # d_model-long weighted row update (4 d H flops, on the matrix cores with the fp32 operand split
+        # into 16-bit parts); the hidden rows are read twice.  Priced against HBM, on its own bytes.
         flops = 4.0 * d * cfg.n_heads * hidden_tokens
         hid_bytes = 2.0 * d * e * hidden_tokens
-        t_alu, t_hbm = flops / (PEAK_VALU_F32_TFLOPS * 1e12), (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
-        if t_alu >= t_hbm:
-            ach = flops / (kern_avg_ms * 1e-3) / 1e12
-            roof = {"bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": None}
-        else:
-            ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
-            roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": ach / PEAK_HBM_GBS, "traffic": None}
+        ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey + "@absorbed")}
     elif t_mfma >= t_hbm:
         ach = flops / (kern_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
@@ -174,7 +168,7 @@ def main():
     mfma_items = rn.info.n_hidden_items > 0 and rn.info.hidden_impl == 2
     kname = "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel"
     if rn.info.hidden_impl == 3 and hidden_tokens > 0:
-        kname = "apt_absorb_{q,score,stats,pv,out}_kernel + apt_items_kernel (one event pair around all six)"
+        kname = "apt_absorb_{q,score,stats,pv,out,final}_kernel + apt_items_kernel (one event pair around all seven)"
     roof.update({"kernel": kname, "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
                  "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
 
@@ -243,7 +237,8 @@ def time_ratio(cfg, ratio, args):
     c = wl.with_ratio(cfg, ratio)
     batch = wl.make_batch(c)
     layer = wl.make_layer(batch, workers=min(16, os.cpu_count() or 8))
-    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk)
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk,
+                      hidden_impl={"auto": 0, "valu": 1, "mfma": 2, "absorbed": 3}[args.hidden_impl])
     dl = rn.upload(layer)
     for _ in range(args.warmup):
         rn.plan()

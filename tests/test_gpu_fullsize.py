@@ -33,12 +33,12 @@ def _sample_pairs(batch, n_random, seed):
     return sorted(set(pairs))
 
 
-def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2):
+def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_impl=0):
     from paper_2504_07494_amd.harness import DecodeRunner
-    print(f"[case] full size {cfg.name} ratio={cfg.hidden_ratio}", flush=True)
+    print(f"[case] full size {cfg.name} ratio={cfg.hidden_ratio} hidden_impl={hidden_impl}", flush=True)
     batch = wl.make_batch(cfg)
     layer = wl.make_layer(batch, workers=16)
-    rn = DecodeRunner(batch)
+    rn = DecodeRunner(batch, hidden_impl=hidden_impl)
     dl = rn.upload(layer)
     rn.run(dl)
     got = rn.out_f64()
@@ -64,6 +64,18 @@ def test_opt13b_layer(oracle):
 
 def test_opt30b_layer_permuted_pages(oracle):
     _run_and_check(oracle, wl.CONFIGS["opt30b"], n_random=16)
+
+
+def test_opt13b_layer_absorbed_weight_path(oracle):
+    from paper_2504_07494_amd import binding as ab
+    _run_and_check(oracle, wl.CONFIGS["opt13b"], n_random=24, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+
+
+def test_opt13b_bf16_all_hidden_absorbed_weight_path(oracle):
+    from dataclasses import replace
+    from paper_2504_07494_amd import binding as ab
+    cfg = replace(wl.with_ratio(wl.CONFIGS["opt13b"], 1.0), dtype="bf16")
+    _run_and_check(oracle, cfg, n_random=12, hidden_impl=ab.APT_HIDDEN_ABSORBED)
 
 
 @pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])

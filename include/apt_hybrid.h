@@ -66,7 +66,8 @@ typedef enum apt_status {
     APT_EDTYPE = -3,     /* unknown dtype / unsupported out_dtype                 */
     APT_EWORKSPACE = -4, /* workspace or plan buffer too small                    */
     APT_EHIP = -5,       /* a HIP runtime call failed                             */
-    APT_ERANGE = -6      /* a block id or length is out of range                  */
+    APT_ERANGE = -6,     /* a block id or length is out of range                  */
+    APT_EFULL = -7       /* not enough unused blocks in the pool (nothing changed) */
 } apt_status;
 
 enum { APT_F32 = 0, APT_F16 = 1, APT_BF16 = 2 };
@@ -233,6 +234,42 @@ int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void
                                  void* ev_begin, void* ev_end);
 
 /*
+ * Hybrid cache assigner: host-side bookkeeping of the unified block pool (Section 4.3,
+ * "Tailored Global Memory Pool" and "Cache Block Allocation").  The pool has n_blocks blocks;
+ * each holds the K, V or hidden vectors of block_size consecutive token positions of one
+ * request, so a KV-kind request of n tokens occupies 2*ceil(n/block_size) blocks and a
+ * hidden-kind request half of that (the (1 - beta/2) m of Definition 1).  Requests live in
+ * numbered slots (0 .. max_requests-1).  A request's cache map lists its blocks in position
+ * order; blocks are picked on demand by scanning for unused blocks, lowest block id first (for a
+ * KV-kind request the K block of a position range is taken before its V block).  All memory is
+ * host memory owned by the handle; nothing here touches the device.
+ *   apt_pool_assign       new request in an empty slot: blocks for n_tokens positions
+ *   apt_pool_extend       grow a request to n_tokens (>= its current length); takes blocks
+ *                         only when a block boundary is crossed
+ *   apt_pool_release      return all blocks of the slot, empty the slot
+ *   apt_pool_switch_kind  discard the cache and take blocks for the same length in the other
+ *                         kind (Section 5: the caller then recomputes the contents by a prefill)
+ *   apt_pool_export       block_tables int32 [B][2][max_blocks_per_req] (-1 = no block),
+ *                         ctx_lens int32 [B], cache_kind uint8 [B] of the listed slots, in the
+ *                         layout the attention and cache-write calls take (host arrays)
+ *   apt_pool_blocks_needed  blocks a request of n_tokens occupies in the given kind
+ * Errors: APT_EINVAL (null, bad slot, slot empty / in use, shrinking), APT_ERANGE (more than
+ * max_blocks_per_req blocks), APT_EFULL (not enough unused blocks; the pool is unchanged).
+ */
+typedef struct apt_pool apt_pool;
+int apt_pool_create(int64_t n_blocks, int32_t block_size, int32_t max_blocks_per_req, int32_t max_requests,
+                    apt_pool** out);
+void apt_pool_destroy(apt_pool* pool);
+int apt_pool_free_blocks(const apt_pool* pool, int64_t* n_free);
+int apt_pool_blocks_needed(const apt_pool* pool, uint8_t kind, int32_t n_tokens, int64_t* n_blocks);
+int apt_pool_assign(apt_pool* pool, int32_t slot, uint8_t kind, int32_t n_tokens);
+int apt_pool_extend(apt_pool* pool, int32_t slot, int32_t n_tokens);
+int apt_pool_release(apt_pool* pool, int32_t slot);
+int apt_pool_switch_kind(apt_pool* pool, int32_t slot, uint8_t new_kind);
+int apt_pool_export(const apt_pool* pool, const int32_t* slots, int B, int32_t* block_tables, int32_t* ctx_lens,
+                    uint8_t* cache_kind);
+
+/*
  * Cache append: writes the vectors of the token just processed into the request's cache
  * blocks, with the layout change fused into the write (the paper's block-wise cache I/O
  * kernel, Section 5.1; block placement per Section 4.3).  For request r with
@@ -250,6 +287,23 @@ int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void
 int apt_cache_append(const apt_shape* s, int B, const void* x_new, const void* k_new, const void* v_new,
                      void* k_pages, void* v_pages, void* hidden_pages, const int32_t* block_tables,
                      const int32_t* ctx_lens_dev, const uint8_t* cache_kind_dev, void* stream);
+
+/*
+ * Cache write of a run of new tokens per request: the prefill's cache write (all prompt
+ * positions at once, both cache kinds; Section 2.2 and Section 5.1) and the general form of
+ * apt_cache_append.  Request r has n_r = new_offsets[r+1] - new_offsets[r] new tokens; their
+ * vectors are rows new_offsets[r] .. new_offsets[r+1]-1 of x_new [rows][d_model] (hidden kind)
+ * or k_new, v_new [rows][n_heads][head_dim] (KV kind) and go to positions
+ * ctx_lens[r] - n_r .. ctx_lens[r] - 1 of the request's cache map (ctx_lens counts the tokens
+ * AFTER the write), with the same layout change as apt_cache_append.  n_r may be 0.
+ * new_offsets_dev int32 [B+1] (device, non-decreasing, first entry 0); max_new_tokens >= every
+ * n_r sizes the launch (host value).  Pointer rules, aliasing rules and errors as for
+ * apt_cache_append; APT_ERANGE if max_new_tokens exceeds 524280.  One launch.
+ */
+int apt_cache_write(const apt_shape* s, int B, const int32_t* new_offsets_dev, int32_t max_new_tokens,
+                    const void* x_new, const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                    void* hidden_pages, const int32_t* block_tables, const int32_t* ctx_lens_dev,
+                    const uint8_t* cache_kind_dev, void* stream);
 
 /*
  * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16; device

@@ -306,3 +306,43 @@ int apt_oracle_append(const oracle_shape* s, int B, const void* x_new, const voi
     }
     return 0;
 }
+
+/*
+ * Cache write of a run of new tokens per request (the prefill's cache write; Section 2.2,
+ * Section 4.3 for the placement).  Request r has n_r = new_offsets[r+1] - new_offsets[r] new
+ * tokens whose vectors are rows new_offsets[r].. of x_new / k_new / v_new; they go to positions
+ * ctx_lens[r] - n_r .. ctx_lens[r] - 1, one position at a time by the same rule as
+ * apt_oracle_append.  Returns 0, -1 on a bad argument.
+ */
+int apt_oracle_write(const oracle_shape* s, int B, const int32_t* new_offsets, const void* x_new, const void* k_new,
+                     const void* v_new, void* k_pages, void* v_pages, void* hidden_pages,
+                     const int32_t* block_tables, const int32_t* ctx_lens, const uint8_t* cache_kind) {
+    const int d = s->d_model, H = s->n_heads, hd = s->head_dim, bs = s->block_size;
+    const int eb = s->dtype == ORACLE_F32 ? 4 : 2;
+    const int64_t blk_elems = (int64_t)bs * d;
+    for (int r = 0; r < B; ++r) {
+        const int n_new = new_offsets[r + 1] - new_offsets[r];
+        if (n_new < 0 || n_new > ctx_lens[r] || cache_kind[r] > 1) return -1;
+        for (int t = 0; t < n_new; ++t) {
+            const int j = ctx_lens[r] - n_new + t;
+            const int64_t row = new_offsets[r] + t;
+            int32_t b0, b1, slot;
+            apt_oracle_locate(block_tables, s->max_blocks, bs, r, 0, j, &b0, &slot);
+            if (cache_kind[r] == ORACLE_HIDDEN) {
+                for (int i = 0; i < d; ++i)
+                    memcpy((char*)hidden_pages + (b0 * blk_elems + (int64_t)slot * d + i) * eb,
+                           (const char*)x_new + (row * d + i) * eb, eb);
+            } else {
+                apt_oracle_locate(block_tables, s->max_blocks, bs, r, 1, j, &b1, &slot);
+                for (int h = 0; h < H; ++h)
+                    for (int c = 0; c < hd; ++c) {
+                        const int64_t off = ((int64_t)h * bs + slot) * hd + c;
+                        const int64_t src = (row * H + h) * hd + c;
+                        memcpy((char*)k_pages + (b0 * blk_elems + off) * eb, (const char*)k_new + src * eb, eb);
+                        memcpy((char*)v_pages + (b1 * blk_elems + off) * eb, (const char*)v_new + src * eb, eb);
+                    }
+            }
+        }
+    }
+    return 0;
+}

@@ -112,3 +112,16 @@ def append(shape, x_new, k_new, v_new, k_pages, v_pages, hidden_pages, block_tab
                                  _p(cache_kind))
     if rc != 0:
         raise ValueError("apt_oracle_append: bad argument")
+
+
+def write(shape, new_offsets, x_new, k_new, v_new, k_pages, v_pages, hidden_pages, block_tables, ctx_lens, cache_kind):
+    """In-place cache write of runs of new tokens (positions ctx_lens[r] - n_r .. ctx_lens[r] - 1)."""
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    cache_kind = np.ascontiguousarray(cache_kind, dtype=np.uint8)
+    block_tables = np.ascontiguousarray(block_tables, dtype=np.int32)
+    new_offsets = np.ascontiguousarray(new_offsets, dtype=np.int32)
+    rc = lib().apt_oracle_write(C.byref(shape), C.c_int(len(ctx_lens)), _p(new_offsets), _p(x_new), _p(k_new), _p(v_new),
+                                _p(k_pages), _p(v_pages), _p(hidden_pages), _p(block_tables), _p(ctx_lens),
+                                _p(cache_kind))
+    if rc != 0:
+        raise ValueError("apt_oracle_write: bad argument")

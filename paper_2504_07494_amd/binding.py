@@ -17,12 +17,14 @@ LIB_PATH = os.path.join(_HERE, "libapt_hybrid.so")
 APT_F32, APT_F16, APT_BF16 = 0, 1, 2
 APT_KIND_KV, APT_KIND_HIDDEN = 0, 1
 APT_HIDDEN_AUTO, APT_HIDDEN_VALU, APT_HIDDEN_MFMA, APT_HIDDEN_ABSORBED = 0, 1, 2, 3
-APT_OK, APT_EINVAL, APT_ESHAPE, APT_EDTYPE, APT_EWORKSPACE, APT_EHIP, APT_ERANGE = 0, -1, -2, -3, -4, -5, -6
+APT_OK, APT_EINVAL, APT_ESHAPE, APT_EDTYPE, APT_EWORKSPACE, APT_EHIP, APT_ERANGE, APT_EFULL = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 
 EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt_plan_get_info", "apt_plan_upload",
            "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
-           "apt_hybrid_decode_attn_timed", "apt_cache_append", "apt_copy_bytes", "apt_probe_mfma"]
+           "apt_hybrid_decode_attn_timed", "apt_cache_append", "apt_cache_write", "apt_copy_bytes", "apt_probe_mfma",
+           "apt_pool_create", "apt_pool_destroy", "apt_pool_free_blocks", "apt_pool_blocks_needed", "apt_pool_assign",
+           "apt_pool_extend", "apt_pool_release", "apt_pool_switch_kind", "apt_pool_export"]
 
 
 class apt_shape(C.Structure):
@@ -59,6 +61,7 @@ def lib():
         _lib.apt_strerror.argtypes = [C.c_int]
         for name in EXPORTS[1:]:
             getattr(_lib, name).restype = C.c_int
+        _lib.apt_pool_destroy.restype = None
     return _lib
 
 
@@ -162,6 +165,62 @@ def apt_cache_append(shape, B, x_new, k_new, v_new, k_pages, v_pages, hidden_pag
     _check(lib().apt_cache_append(C.byref(shape), C.c_int(B), _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(k_pages),
                                   _ptr(v_pages), _ptr(hidden_pages), _ptr(block_tables), _ptr(ctx_lens_dev),
                                   _ptr(cache_kind_dev), C.c_void_p(stream)), "apt_cache_append")
+
+
+def apt_cache_write(shape, B, new_offsets_dev, max_new_tokens, x_new, k_new, v_new, k_pages, v_pages, hidden_pages,
+                    block_tables, ctx_lens_dev, cache_kind_dev, stream=0):
+    _check(lib().apt_cache_write(C.byref(shape), C.c_int(B), _ptr(new_offsets_dev), C.c_int32(max_new_tokens),
+                                 _ptr(x_new), _ptr(k_new), _ptr(v_new), _ptr(k_pages), _ptr(v_pages),
+                                 _ptr(hidden_pages), _ptr(block_tables), _ptr(ctx_lens_dev), _ptr(cache_kind_dev),
+                                 C.c_void_p(stream)), "apt_cache_write")
+
+
+# --- hybrid cache assigner (host-side pool bookkeeping); `pool` is the opaque handle --------------
+def apt_pool_create(n_blocks, block_size, max_blocks_per_req, max_requests) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(lib().apt_pool_create(C.c_int64(n_blocks), C.c_int32(block_size), C.c_int32(max_blocks_per_req),
+                                 C.c_int32(max_requests), C.byref(h)), "apt_pool_create")
+    return h
+
+
+def apt_pool_destroy(pool):
+    lib().apt_pool_destroy(pool)
+
+
+def apt_pool_free_blocks(pool) -> int:
+    n = C.c_int64()
+    _check(lib().apt_pool_free_blocks(pool, C.byref(n)), "apt_pool_free_blocks")
+    return n.value
+
+
+def apt_pool_blocks_needed(pool, kind, n_tokens) -> int:
+    n = C.c_int64()
+    _check(lib().apt_pool_blocks_needed(pool, C.c_uint8(kind), C.c_int32(n_tokens), C.byref(n)), "apt_pool_blocks_needed")
+    return n.value
+
+
+def apt_pool_assign(pool, slot, kind, n_tokens):
+    _check(lib().apt_pool_assign(pool, C.c_int32(slot), C.c_uint8(kind), C.c_int32(n_tokens)), "apt_pool_assign")
+
+
+def apt_pool_extend(pool, slot, n_tokens):
+    _check(lib().apt_pool_extend(pool, C.c_int32(slot), C.c_int32(n_tokens)), "apt_pool_extend")
+
+
+def apt_pool_release(pool, slot):
+    _check(lib().apt_pool_release(pool, C.c_int32(slot)), "apt_pool_release")
+
+
+def apt_pool_switch_kind(pool, slot, new_kind):
+    _check(lib().apt_pool_switch_kind(pool, C.c_int32(slot), C.c_uint8(new_kind)), "apt_pool_switch_kind")
+
+
+def apt_pool_export(pool, slots: np.ndarray, block_tables: np.ndarray, ctx_lens: np.ndarray, cache_kind: np.ndarray):
+    """Fills the host arrays block_tables int32 [B][2][max_blocks], ctx_lens int32 [B], cache_kind uint8 [B]."""
+    assert slots.dtype == np.int32 and block_tables.dtype == np.int32 and ctx_lens.dtype == np.int32
+    assert cache_kind.dtype == np.uint8
+    _check(lib().apt_pool_export(pool, _ptr(slots), C.c_int(len(slots)), _ptr(block_tables), _ptr(ctx_lens),
+                                 _ptr(cache_kind)), "apt_pool_export")
 
 
 def apt_copy_bytes(dst, src, nbytes, stream=0):

@@ -852,6 +852,41 @@ __global__ __launch_bounds__(kThreads) void apt_append_kernel(const char* x_new,
     }
 }
 
+// Cache write of a run of new tokens per request (prefill, or several decoded tokens at once): grid
+// (request, group of kWriteTokens new tokens), 16-byte units as in the append kernel.
+constexpr int kWriteTokens = 8;
+__global__ __launch_bounds__(kThreads) void apt_write_kernel(const int32_t* new_offsets, const char* x_new, const char* k_new,
+                                                             const char* v_new, char* k_pages, char* v_pages,
+                                                             char* hidden_pages, const int32_t* block_tables,
+                                                             const int32_t* ctx_lens, const uint8_t* cache_kind, int d, int hd,
+                                                             int bs, int log2_bs, int max_blocks, int eb) {
+    const int r = blockIdx.x;
+    const int row0 = new_offsets[r], n_new = new_offsets[r + 1] - row0;
+    const int first = ctx_lens[r] - n_new;              // position of the first new token
+    const int64_t blk_bytes = (int64_t)bs * d * eb;
+    const int row_units = d * eb / 16, head_units = hd * eb / 16;
+    const bool hidden = cache_kind[r] == APT_KIND_HIDDEN;
+    for (int t = blockIdx.y * kWriteTokens; t < min(n_new, (int)(blockIdx.y + 1) * kWriteTokens); ++t) {
+        const int j = first + t, slot = j & (bs - 1);
+        const int64_t e0 = (int64_t)r * 2 * max_blocks + (j >> log2_bs);
+        const int64_t src = (int64_t)(row0 + t) * row_units;
+        if (hidden) {
+            char* dst = hidden_pages + (int64_t)block_tables[e0] * blk_bytes + (int64_t)slot * d * eb;
+            for (int u = threadIdx.x; u < row_units; u += kThreads)
+                *(uint4*)(dst + (int64_t)u * 16) = *(const uint4*)(x_new + (src + u) * 16);
+        } else {
+            char* kd = k_pages + (int64_t)block_tables[e0] * blk_bytes;
+            char* vd = v_pages + (int64_t)block_tables[e0 + max_blocks] * blk_bytes;
+            for (int u = threadIdx.x; u < row_units; u += kThreads) {
+                const int h = u / head_units, cu = u % head_units;
+                const int64_t off = (((int64_t)h * bs + slot) * hd) * eb + (int64_t)cu * 16;
+                *(uint4*)(kd + off) = *(const uint4*)(k_new + (src + u) * 16);
+                *(uint4*)(vd + off) = *(const uint4*)(v_new + (src + u) * 16);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const uint4* src, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
@@ -1008,6 +1043,27 @@ extern "C" int apt_cache_append(const apt_shape* s, int B, const void* x_new, co
                        (const char*)k_new, (const char*)v_new, (char*)k_pages, (char*)v_pages, (char*)hidden_pages,
                        block_tables, ctx_lens_dev, cache_kind_dev, rs.s.d_model, rs.s.head_dim, rs.s.block_size, log2_bs,
                        rs.s.max_blocks_per_req, rs.elem_bytes);
+    return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
+}
+
+extern "C" int apt_cache_write(const apt_shape* s, int B, const int32_t* new_offsets_dev, int32_t max_new_tokens,
+                               const void* x_new, const void* k_new, const void* v_new, void* k_pages, void* v_pages,
+                               void* hidden_pages, const int32_t* block_tables, const int32_t* ctx_lens_dev,
+                               const uint8_t* cache_kind_dev, void* stream) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (B < 1 || max_new_tokens < 1 || !new_offsets_dev || !block_tables || !ctx_lens_dev || !cache_kind_dev) return APT_EINVAL;
+    if (!x_new && !k_new && !v_new) return APT_EINVAL;
+    if ((x_new && !hidden_pages) || ((k_new || v_new) && (!k_new || !v_new || !k_pages || !v_pages))) return APT_EINVAL;
+    int log2_bs = 0;
+    while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
+    const unsigned groups = (unsigned)((max_new_tokens + kWriteTokens - 1) / kWriteTokens);
+    if (groups > 65535u) return APT_ERANGE;
+    hipLaunchKernelGGL(apt_write_kernel, dim3(B, groups), dim3(kThreads), 0, (hipStream_t)stream, new_offsets_dev,
+                       (const char*)x_new, (const char*)k_new, (const char*)v_new, (char*)k_pages, (char*)v_pages,
+                       (char*)hidden_pages, block_tables, ctx_lens_dev, cache_kind_dev, rs.s.d_model, rs.s.head_dim,
+                       rs.s.block_size, log2_bs, rs.s.max_blocks_per_req, rs.elem_bytes);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 

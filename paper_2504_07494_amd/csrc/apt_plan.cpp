@@ -14,6 +14,7 @@ extern "C" const char* apt_strerror(int status) {
     case APT_EWORKSPACE: return "buffer too small";
     case APT_EHIP: return "HIP runtime error";
     case APT_ERANGE: return "value out of range";
+    case APT_EFULL: return "not enough unused cache blocks";
     default: return "unknown status";
     }
 }

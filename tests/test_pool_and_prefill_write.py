@@ -1,0 +1,279 @@
+"""Hybrid cache assigner (host-side pool bookkeeping) and the prefill's cache write: the C ABI
+against the plain rule / the oracle, pins on the paper's worked example, and a multi-step serving
+loop on the GPU (assign, prefill write, decode steps with append and attention, release, switch
+of cache kind) checked against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import pool_oracle as pool_o
+from paper_2504_07494_amd import binding as ab
+from paper_2504_07494_amd import workloads as wl
+from tests.test_oracle_pins import _read_pool_example
+
+KV, HID = wl.KIND_KV, wl.KIND_HIDDEN
+
+
+def _export(pool, slots, max_blocks):
+    slots = np.asarray(slots, dtype=np.int32)
+    bt = np.empty((len(slots), 2, max_blocks), dtype=np.int32)
+    lens = np.empty(len(slots), dtype=np.int32)
+    kinds = np.empty(len(slots), dtype=np.uint8)
+    ab.apt_pool_export(pool, slots, bt, lens, kinds)
+    return bt, lens, kinds
+
+
+def test_pool_storage_law_and_growth_on_the_papers_example_sizes():
+    # Section 4.3 example: 16 blocks of 4 positions; A = KV cache, 11 tokens -> 3 K + 3 V blocks;
+    # B = hidden cache, 14 tokens -> 4 blocks (half of what a KV cache of 14 tokens would take)
+    ex = _read_pool_example()
+    pool = ab.apt_pool_create(ex["pool_blocks"], ex["block_size"], 8, 4)
+    try:
+        ab.apt_pool_assign(pool, 0, KV, 11)
+        ab.apt_pool_assign(pool, 1, HID, 14)
+        assert ab.apt_pool_free_blocks(pool) == 16 - len(ex["A"]["k_blocks"]) - len(ex["A"]["v_blocks"]) - len(ex["B"]["h_blocks"])
+        assert ab.apt_pool_blocks_needed(pool, HID, 14) * 2 == ab.apt_pool_blocks_needed(pool, KV, 14)
+        bt, lens, kinds = _export(pool, [0, 1], 8)
+        used = [b for b in bt.reshape(-1) if b >= 0]
+        assert len(used) == len(set(used)) == 10 and lens.tolist() == [11, 14] and kinds.tolist() == [KV, HID]
+        assert (bt[0, 0, :3] >= 0).all() and (bt[0, 1, :3] >= 0).all() and (bt[0, :, 3:] == -1).all()
+        assert (bt[1, 0, :4] >= 0).all() and (bt[1, 1] == -1).all()
+        ab.apt_pool_extend(pool, 0, 12)                       # still inside the third block
+        assert ab.apt_pool_free_blocks(pool) == 6
+        ab.apt_pool_extend(pool, 0, 13)                       # a new K block and a new V block
+        assert ab.apt_pool_free_blocks(pool) == 4
+        ab.apt_pool_extend(pool, 1, 17)                       # one new hidden block
+        assert ab.apt_pool_free_blocks(pool) == 3
+        with pytest.raises(ab.AptError) as e:                 # 17 tokens as KV cache need 10 blocks, 3 + 5 are there
+            ab.apt_pool_switch_kind(pool, 1, KV)
+        assert e.value.status == ab.APT_EFULL and ab.apt_pool_free_blocks(pool) == 3
+        ab.apt_pool_switch_kind(pool, 0, HID)                 # 13 tokens: 8 blocks back, 4 taken
+        assert ab.apt_pool_free_blocks(pool) == 7
+        ab.apt_pool_release(pool, 1)
+        assert ab.apt_pool_free_blocks(pool) == 12
+    finally:
+        ab.apt_pool_destroy(pool)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_pool_matches_the_plain_rule_over_random_operation_sequences(seed):
+    g = np.random.default_rng(seed)
+    n_blocks, bs, mb, nslots = 97, 4, 12, 10
+    pool = ab.apt_pool_create(n_blocks, bs, mb, nslots)
+    ref = pool_o.Pool(n_blocks, bs)
+    live = {}
+    try:
+        for step in range(600):
+            op = g.integers(5)
+            slot = int(g.integers(nslots))
+            try:
+                if op == 0 and slot not in live:
+                    kind, n = int(g.integers(2)), int(g.integers(1, mb * bs + 1))
+                    try:
+                        ref.assign(slot, kind, n)
+                        want = None
+                    except pool_o.Full:
+                        want = ab.APT_EFULL
+                    if want is None:
+                        ab.apt_pool_assign(pool, slot, kind, n)
+                        live[slot] = n
+                    else:
+                        with pytest.raises(ab.AptError) as e:
+                            ab.apt_pool_assign(pool, slot, kind, n)
+                        assert e.value.status == want
+                elif op in (1, 2) and slot in live:
+                    n = min(mb * bs, live[slot] + int(g.integers(0, 7)))
+                    try:
+                        ref.extend(slot, n)
+                        ab.apt_pool_extend(pool, slot, n)
+                        live[slot] = n
+                    except pool_o.Full:
+                        with pytest.raises(ab.AptError) as e:
+                            ab.apt_pool_extend(pool, slot, n)
+                        assert e.value.status == ab.APT_EFULL
+                elif op == 3 and slot in live:
+                    ref.release(slot)
+                    ab.apt_pool_release(pool, slot)
+                    del live[slot]
+                elif op == 4 and slot in live:
+                    new_kind = 1 - ref.requests[slot]["kind"]
+                    try:
+                        ref.switch_kind(slot, new_kind)
+                        ab.apt_pool_switch_kind(pool, slot, new_kind)
+                    except pool_o.Full:
+                        with pytest.raises(ab.AptError) as e:
+                            ab.apt_pool_switch_kind(pool, slot, new_kind)
+                        assert e.value.status == ab.APT_EFULL
+            finally:
+                pass
+            assert ab.apt_pool_free_blocks(pool) == len(ref.unused)
+            if live and step % 7 == 0:
+                slots = sorted(live)
+                bt, lens, kinds = _export(pool, slots, mb)
+                wbt, wlens, wkinds = ref.export(slots, mb)
+                assert bt.tolist() == wbt and lens.tolist() == wlens and kinds.tolist() == wkinds
+                used = [b for b in bt.reshape(-1) if b >= 0]
+                assert len(used) == len(set(used)) == n_blocks - len(ref.unused)     # no block in two maps
+    finally:
+        ab.apt_pool_destroy(pool)
+
+
+def test_pool_rejects_bad_arguments():
+    pool = ab.apt_pool_create(8, 4, 2, 2)
+    try:
+        for call in (lambda: ab.apt_pool_assign(pool, 2, KV, 1), lambda: ab.apt_pool_assign(pool, 0, 2, 1),
+                     lambda: ab.apt_pool_assign(pool, 0, KV, 0), lambda: ab.apt_pool_extend(pool, 0, 3),
+                     lambda: ab.apt_pool_release(pool, 1), lambda: ab.apt_pool_switch_kind(pool, 1, HID)):
+            with pytest.raises(ab.AptError) as e:
+                call()
+            assert e.value.status == ab.APT_EINVAL
+        with pytest.raises(ab.AptError) as e:
+            ab.apt_pool_assign(pool, 0, HID, 9)               # 3 blocks > max_blocks_per_req
+        assert e.value.status == ab.APT_ERANGE
+        ab.apt_pool_assign(pool, 0, KV, 8)
+        with pytest.raises(ab.AptError) as e:
+            ab.apt_pool_assign(pool, 0, KV, 1)                # slot in use
+        assert e.value.status == ab.APT_EINVAL
+        with pytest.raises(ab.AptError) as e:
+            ab.apt_pool_extend(pool, 0, 7)                    # shrinking
+        assert e.value.status == ab.APT_EINVAL
+    finally:
+        ab.apt_pool_destroy(pool)
+    with pytest.raises(ab.AptError):
+        ab.apt_pool_create(0, 4, 2, 2)
+
+
+def _rows(cfg, n, seed):
+    g = np.random.default_rng(seed)
+    x = wl.round_to_dtype(g.standard_normal((n, cfg.d_model), dtype=np.float32), cfg.dtype)
+    k = wl.round_to_dtype(g.standard_normal((n, cfg.n_heads, cfg.head_dim), dtype=np.float32), cfg.dtype)
+    v = wl.round_to_dtype(g.standard_normal((n, cfg.n_heads, cfg.head_dim), dtype=np.float32), cfg.dtype)
+    return x, k, v
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_oracle_range_write_equals_repeated_single_token_appends(oracle, dtype):
+    # a run of n_r tokens written at once = n_r appends with growing lengths (the single-token
+    # append is pinned on the paper's example and against the generator's layout accessors)
+    from tests.helpers import oracle_shape
+    cfg = wl.small_config(batch=6, len_hi=45, dtype=dtype, poison=False)
+    b = wl.make_batch(cfg)
+    l = wl.make_layer(b)
+    g = np.random.default_rng(7)
+    n_new = np.array([min(int(b.ctx_lens[r]), int(g.integers(0, 20))) for r in range(b.B)], dtype=np.int32)
+    n_new[0] = b.ctx_lens[0]                                   # a whole prompt
+    n_new[1] = 0                                               # nothing new
+    off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    x, k, v = _rows(cfg, int(off[-1]), 8)
+    sh = oracle_shape(oracle, b)
+    got = l.pool.copy()
+    oracle.write(sh, off, x, k, v, got, got, got, b.block_tables, b.ctx_lens, b.cache_kind)
+    want = l.pool.copy()
+    for t in range(int(n_new.max())):
+        rows = [r for r in range(b.B) if t < n_new[r]]
+        sub_bt = b.block_tables[rows]
+        lens = np.array([b.ctx_lens[r] - n_new[r] + t + 1 for r in rows], dtype=np.int32)
+        src = [off[r] + t for r in rows]
+        oracle.append(oracle.shape_of(cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.block_size, cfg.dtype, b.max_blocks, 1.0),
+                      x[src], k[src], v[src], want, want, want, sub_bt, lens, b.cache_kind[rows])
+    assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
+    assert not np.array_equal(got.view(np.uint8), l.pool.view(np.uint8))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,hd,H,bs", [("f16", 128, 4, 16), ("f32", 64, 4, 8)])
+def test_gpu_serving_loop_pool_prefill_write_append_attention(oracle, dtype, hd, H, bs):
+    """Requests arrive (assign + prefill write), decode for a few steps (extend + append + attention),
+    leave (release) and change cache kind (switch + re-written cache); blocks are reused.  Every
+    step's cache bytes equal the oracle's, every step's attention output matches the oracle."""
+    import torch
+    from paper_2504_07494_amd.harness import _to_dev
+    print(f"[case] serving loop {dtype} hd={hd} bs={bs}", flush=True)
+    dev = torch.device("cuda:0")
+    d = hd * H
+    mb, n_blocks, nslots = 12, 150, 8
+    cfg = wl.small_config(name="loop", dtype=dtype, d_model=d, n_heads=H, head_dim=hd, block_size=bs, batch=nslots,
+                          len_lo=1, len_hi=mb * bs, hidden_ratio=0.5, poison=False)
+    g = np.random.default_rng(11)
+    scale = 1.0 / np.sqrt(hd)
+    shape = ab.make_shape(d, H, hd, bs, dtype, mb, scale)
+    osh = oracle.shape_of(d, H, hd, bs, dtype, mb, scale)
+    e = wl.ELEM_BYTES[dtype]
+    # weights of the layer
+    tmpl = wl.make_layer(wl.make_batch(cfg, np.ones(1, dtype=np.int32), np.array([HID], dtype=np.uint8)))
+    W_K, W_V, b_K, b_V = tmpl.W_K, tmpl.W_V, tmpl.b_K, tmpl.b_V
+    dW_K, dW_V, db_K, db_V = (_to_dev(a, dev) for a in (W_K, W_V, b_K, b_V))
+    raw = np.uint16 if e == 2 else np.float32
+    host_pool = np.zeros((n_blocks, bs * d), dtype=raw)                      # the oracle's pool
+    if e == 2:
+        host_pool[...] = 0x7e00 if dtype == "f16" else 0x7fc0               # NaN in every slot not yet written
+    else:
+        host_pool[...] = np.nan
+    dev_pool = _to_dev(host_pool, dev)
+    packed = None
+    if dtype != "f32" and hd == 128:
+        packed = torch.empty(ab.apt_packed_weight_bytes(shape), dtype=torch.uint8, device=dev)
+        ab.apt_pack_weights(shape, dW_K, dW_V, packed, 0)
+    pool = ab.apt_pool_create(n_blocks, bs, mb, nslots)
+    live = {}
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    plan_bytes = ab.apt_plan_max_bytes(shape, nslots, mb * bs)
+    plan_host = np.empty(plan_bytes // 4, dtype=np.int32)
+    plan_dev = torch.empty(plan_bytes // 4, dtype=torch.int32, device=dev)
+    try:
+        for step in range(14):
+            # arrivals and departures
+            new_slots = []
+            for slot in range(nslots):
+                if slot not in live and g.random() < 0.5:
+                    n = int(g.integers(1, 5 * bs))
+                    ab.apt_pool_assign(pool, slot, int(g.integers(2)), n)
+                    live[slot] = n
+                    new_slots.append(slot)
+                elif slot in live and slot not in new_slots and g.random() < 0.15:
+                    ab.apt_pool_release(pool, slot)
+                    del live[slot]
+                elif slot in live and g.random() < 0.15:                     # cache kind switch: cache rebuilt
+                    _, _, kk = _export(pool, [slot], mb)
+                    ab.apt_pool_switch_kind(pool, slot, 1 - int(kk[0]))
+                    new_slots.append(slot)
+            if not live:
+                continue
+            # decode step: every request that is not new grows by one token
+            for slot in live:
+                if slot not in new_slots and live[slot] < mb * bs:
+                    live[slot] += 1
+                    ab.apt_pool_extend(pool, slot, live[slot])
+            slots = sorted(live)
+            B = len(slots)
+            bt, lens, kinds = _export(pool, slots, mb)
+            n_new = np.array([live[s] if s in new_slots else (1 if lens[i] == live[s] else 0) for i, s in enumerate(slots)],
+                             dtype=np.int32)
+            for i, s in enumerate(slots):                                     # a request at its length limit gets nothing new
+                if s not in new_slots and live[s] == mb * bs:
+                    n_new[i] = 0
+            off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+            x, k, v = _rows(cfg, max(1, int(off[-1])), 100 + step)
+            oracle.write(osh, off, x, k, v, host_pool, host_pool, host_pool, bt, lens, kinds)
+            d_bt, d_lens, d_kinds = (torch.from_numpy(a).to(dev) for a in (bt, lens, kinds))
+            ab.apt_cache_write(shape, B, torch.from_numpy(off).to(dev), int(n_new.max()) if n_new.max() > 0 else 1,
+                               _to_dev(x, dev), _to_dev(k, dev), _to_dev(v, dev), dev_pool, dev_pool, dev_pool,
+                               d_bt, d_lens, d_kinds, stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(dev_pool.cpu().numpy().view(np.uint8).reshape(-1), host_pool.view(np.uint8).reshape(-1)), step
+            # attention of the step
+            q = wl.round_to_dtype(g.standard_normal((B, H, hd), dtype=np.float32), dtype)
+            info = ab.apt_plan(shape, lens, kinds, plan_host)
+            ab.apt_plan_upload(plan_host, plan_dev, stream)
+            ws = torch.empty(int(info.workspace_bytes), dtype=torch.uint8, device=dev)
+            out = torch.empty((B, H, hd), dtype=torch.float32, device=dev)
+            ab.apt_hybrid_decode_attn(shape, plan_host, plan_dev, _to_dev(q, dev), dev_pool, dev_pool, dev_pool, dW_K, dW_V,
+                                      packed, db_K, db_V, d_bt, out, ws, int(info.workspace_bytes), stream)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().astype(np.float64)
+            want = oracle.attn(osh, q, host_pool, host_pool, host_pool, W_K, b_K, W_V, b_V, bt, lens, kinds).reshape(got.shape)
+            assert np.all(np.isfinite(got)), step
+            err = float(np.max(np.abs(got - want)))
+            print(f"  step {step}: B={B} new={int(off[-1])} free={ab.apt_pool_free_blocks(pool)} max_abs={err:.2e}", flush=True)
+            assert err < 2e-4, (step, err)
+    finally:
+        ab.apt_pool_destroy(pool)

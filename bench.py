@@ -86,8 +86,9 @@ def main():
     ap.add_argument("--pairs-per-thread", type=int, default=8)
     ap.add_argument("--sweep", action="store_true",
                     help="also time hidden-cache ratios 0/25/50/75/100 %% of the same config (adds a 'sweep' list)")
-    ap.add_argument("--probe", choices=["copy", "mfma"], default=None,
-                    help="run only a calibration kernel (plain copy of 1 GiB, or the register-only MFMA loop)")
+    ap.add_argument("--probe", choices=["copy", "mfma", "sched"], default=None,
+                    help="run only a calibration kernel (plain copy of 1 GiB, or the register-only MFMA loop), or time "
+                         "the host-side greedy scheduler at the candidate counts of the paper's scalability table")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -97,6 +98,8 @@ def main():
     from paper_2504_07494_amd import workloads as wl
     from paper_2504_07494_amd.harness import DecodeRunner
 
+    if args.probe == "sched":
+        return run_sched_probe(args)
     if args.probe:
         return run_probe(args)
 
@@ -262,6 +265,32 @@ def time_ratio(cfg, ratio, args):
             "ms_per_step": ms_step, "kernel_ms": kms, "cached_tokens_per_s": batch.total_tokens / (ms_step * 1e-3),
             "mfma_tflops": flops / (kms * 1e-3) / 1e12, "mfma_frac": flops / (kms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS[c.dtype],
             "hbm_gbs": nbytes / (kms * 1e-3) / 1e9, "hbm_frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+
+def run_sched_probe(args):
+    """Section 6.6, scalability table: execution time of the scheduling algorithm against the number of
+    candidate requests (the paper's numbers are from its implementation on its machine: context only).
+    Candidates: contexts U[128, 2048] in blocks of 16, pending times Exp(1 s), memory for 40 % of the
+    KV caches, rho as fitted by --sweep (per block of 16 tokens and request, 40 layers)."""
+    import numpy as np
+    from paper_2504_07494_amd import binding as ab
+    paper_ms = {50: 0.3, 100: 0.5, 200: 1.0, 400: 2.1, 800: 4.8, 1600: 10.8}
+    g = np.random.default_rng(2504)
+    rho = 0.091e-6 * 16 * 40 / 2          # seconds per unit of m (m = 2 blocks per 16 tokens)
+    rows = []
+    for n, ref in paper_ms.items():
+        mem = (2 * -(-g.integers(128, 2049, size=n) // 16)).astype(np.int64)
+        pending = g.exponential(1.0, size=n)
+        limit = int(mem.sum() * 0.4)
+        ab.apt_schedule(pending, mem, limit, n, rho)
+        reps = max(args.steps, 20)
+        t = time.perf_counter()
+        for _ in range(reps):
+            alpha, beta, val = ab.apt_schedule(pending, mem, limit, n, rho)
+        ms = (time.perf_counter() - t) / reps * 1e3
+        rows.append({"candidates": n, "ms": ms, "paper_ms_other_machine": ref, "scheduled": int(alpha.sum()),
+                     "hidden": int(beta.sum()), "value": val})
+    print(json.dumps({"probe": "sched", "unit": "ms per apt_schedule call (host, one thread)", "rows": rows}))
 
 
 def run_probe(args):

@@ -270,6 +270,23 @@ int apt_pool_export(const apt_pool* pool, const int32_t* slots, int B, int32_t* 
                     uint8_t* cache_kind);
 
 /*
+ * Greedy solution of the hybrid-cache scheduling problem (Section 5, Definition 1): choose for
+ * every candidate request i whether it is scheduled (alpha_i) and whether it gets hidden cache
+ * (beta_i), maximising sum alpha_i g_i with g_i = p_i - beta_i * n_unfinished * rho * m_i under
+ * sum (1 - beta_i/2) m_i alpha_i <= mem_limit.  pending[i] = p_i >= 0 (pending time), mem[i] = m_i
+ * (memory of the request's KV cache, any unit, even and >= 2 so that the hidden cache takes
+ * exactly m_i/2), n_unfinished = |W| + |R|, rho = the extra time per unit of memory of a
+ * hidden-cache request (Eq. 6; the slope bench.py --sweep fits).  Candidate schedules and their
+ * marginal gains theta are the two case tables after Definition 1; they are taken by decreasing
+ * theta (ties: lower request index, first increment first) while they fit, a second increment
+ * only after its first, and the result is compared with the best single request.  The value
+ * reached is at least half of the optimum.  alpha, beta: uint8 [n] outputs; value (may be NULL)
+ * receives the objective.  Host only, O(n log n).  Errors: APT_EINVAL.
+ */
+int apt_schedule(const double* pending, const int64_t* mem, int n, int64_t mem_limit, int32_t n_unfinished,
+                 double rho, uint8_t* alpha, uint8_t* beta, double* value);
+
+/*
  * Cache append: writes the vectors of the token just processed into the request's cache
  * blocks, with the layout change fused into the write (the paper's block-wise cache I/O
  * kernel, Section 5.1; block placement per Section 4.3).  For request r with

@@ -24,7 +24,7 @@ EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt
            "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
            "apt_hybrid_decode_attn_timed", "apt_cache_append", "apt_cache_write", "apt_copy_bytes", "apt_probe_mfma",
            "apt_pool_create", "apt_pool_destroy", "apt_pool_free_blocks", "apt_pool_blocks_needed", "apt_pool_assign",
-           "apt_pool_extend", "apt_pool_release", "apt_pool_switch_kind", "apt_pool_export"]
+           "apt_pool_extend", "apt_pool_release", "apt_pool_switch_kind", "apt_pool_export", "apt_schedule"]
 
 
 class apt_shape(C.Structure):
@@ -221,6 +221,18 @@ def apt_pool_export(pool, slots: np.ndarray, block_tables: np.ndarray, ctx_lens:
     assert cache_kind.dtype == np.uint8
     _check(lib().apt_pool_export(pool, _ptr(slots), C.c_int(len(slots)), _ptr(block_tables), _ptr(ctx_lens),
                                  _ptr(cache_kind)), "apt_pool_export")
+
+
+def apt_schedule(pending: np.ndarray, mem: np.ndarray, mem_limit, n_unfinished, rho):
+    """Returns (alpha uint8 [n], beta uint8 [n], value)."""
+    assert pending.dtype == np.float64 and mem.dtype == np.int64 and len(pending) == len(mem)
+    alpha = np.empty(len(pending), dtype=np.uint8)
+    beta = np.empty(len(pending), dtype=np.uint8)
+    val = C.c_double()
+    _check(lib().apt_schedule(_ptr(pending), _ptr(mem), C.c_int(len(pending)), C.c_int64(mem_limit),
+                              C.c_int32(n_unfinished), C.c_double(rho), _ptr(alpha), _ptr(beta), C.byref(val)),
+           "apt_schedule")
+    return alpha, beta, val.value
 
 
 def apt_copy_bytes(dst, src, nbytes, stream=0):

@@ -7,7 +7,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libapt_hybrid.so")
-SOURCES = ["apt_plan.cpp", "apt_pool.cpp", "apt_kernels.hip"]
+SOURCES = ["apt_plan.cpp", "apt_pool.cpp", "apt_sched.cpp", "apt_kernels.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -60,8 +60,6 @@ struct ItemParams {
     void* ab_pp;                  // 16-bit inputs: softmax weights as 16-bit parts, [16 n_hidden_items][parts * 64][32]
     int64_t ab_tokens;            // cached tokens of all hidden-kind requests
     int32_t n_hid_req;
-    int32_t dbg;                  // experiment switches (0 in production)
-    long long* dbg_buf;           // experiment output: per-workgroup clock stamps (null in production)
 };
 
 // ---------------------------------------------------------------------------------
@@ -375,14 +373,7 @@ constexpr int kStageLoads = 8;                         // copies per wave and k-
 // (row >> 2) & 3: measured free of LDS bank conflicts for the 16-byte operand reads of 64-byte rows
 __host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
 
-// EXP: 0 = production.  Timing experiments (wrong results), bit mask: 1 = no MFMAs,
-// 2 = no staging copies inside the k loop, 4 = no X staging copies inside the k loop,
-// 8 = no B-side operand reads inside the k loop, 16 = no W staging copies inside the k loop
-template <int DT, int EXP = 0> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
-    if constexpr ((EXP & 1) != 0) {
-        c[0] += __uint_as_float(a.x ^ b.x);      // keeps the operand reads alive
-        return c;
-    }
+template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
     if constexpr (DT == 1)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8_t, a), __builtin_bit_cast(h8_t, b), c, 0, 0, 0);
     else
@@ -402,7 +393,7 @@ __device__ inline uint4 lds_read16(uint32_t addr) {
 }
 template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int DT, int EXP>
+template <int DT>
 __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
     constexpr int HD = 128;
     extern __shared__ __align__(16) char lds[];
@@ -478,7 +469,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     }
     // copies chunk j (0..3: weights, 4..7: X rows) of this wave's share of k-tile kt into stage st
     auto stage_chunk = [&](int kt, int st, int j) {
-        if constexpr ((EXP & 32) != 0) kt &= 3;      // experiment: re-read the first four k-tiles (cache-resident operands)
         if (j < 4)
             gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + st * kTileBytes + j * 4096);
         else
@@ -490,7 +480,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     }
 
     bool have = qi < q_end;
-    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g] = wall_clock64();
     if (have) {
         it = items[qi];
         lookup(it, ids);
@@ -503,13 +492,12 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #define APT_LOAD_FRAGS(SET, ST, KS, NI, NJ)                                                                 \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
         if (i_ < NI) fa[SET][i_] = lds_read16((a_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
-        if (i_ < NJ && !((EXP & 8) && (KS) + (SET) > 0))                                                    \
-            fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);                       \
+        if (i_ < NJ) fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
     }
 #define APT_MFMA_ALL(SET, NI, NJ)                                                                           \
     _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                     \
         _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                                 \
-            acc[i_][j_] = mfma32<DT, EXP>(fa[SET][i_], fb[SET][j_], acc[i_][j_]);                           \
+            acc[i_][j_] = mfma32<DT>(fa[SET][i_], fb[SET][j_], acc[i_][j_]);                           \
         }                                                                                                   \
     }
     // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
@@ -540,12 +528,11 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                 \
             _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                             \
                 const int m_ = i_ * NJ + j_;              /* 8 copies spread over the NI * NJ MFMAs */      \
-                if (STAGE && (EXP & 2) == 0) {                                                              \
+                if (STAGE) {                                                                                \
                     _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                              \
-                        if (c_ * (NI * NJ) / kStageLoads == m_ && !((EXP & 4) && c_ >= 4) && !((EXP & 16) && c_ < 4)) \
-                            stage_chunk(kt + 4, ST, c_);                                                    \
+                        if (c_ * (NI * NJ) / kStageLoads == m_) stage_chunk(kt + 4, ST, c_);                \
                 }                                                                                           \
-                acc[i_][j_] = mfma32<DT, EXP>(fa[1][i_], fb[1][j_], acc[i_][j_]);                           \
+                acc[i_][j_] = mfma32<DT>(fa[1][i_], fb[1][j_], acc[i_][j_]);                           \
                 __builtin_amdgcn_sched_barrier(0);                                                          \
             }                                                                                               \
         }                                                                                                   \
@@ -724,7 +711,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 
     // ---- then a share of the KV-kind items, longest first
     __syncthreads();
-    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g + 1] = wall_clock64();
     // handed out one by one, so that workgroups that finish their hidden-kind share early take more
     int* ticket_lds = (int*)(lds + 2 * kStages * kTileBytes);
     for (;;) {
@@ -736,7 +722,6 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         kv_item<DT, HD>(p, kv.x, kv.y, kv.z, kv.w, lds);
         __syncthreads();
     }
-    if (p.dbg_buf && tid == 0) p.dbg_buf[4 * g + 2] = wall_clock64();
 }
 
 // ---------------------------------------------------------------------------------
@@ -948,9 +933,9 @@ int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
 #include "apt_absorbed.inc"
 
 // persistent launch: one workgroup per compute unit, a multiple of 8
-template <int DT, int EXP>
+template <int DT>
 int launch_mfma(const ItemParams& p, hipStream_t st) {
-    auto kern = apt_items_mfma_kernel<DT, EXP>;
+    auto kern = apt_items_mfma_kernel<DT>;
     static int n_wg = 0;
     if (n_wg == 0) {
         int dev = 0, cus = 0;
@@ -983,12 +968,7 @@ int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtyp
         return launch_items<DT, HD, 1>(p, v > kv_lds ? v : kv_lds, st);
     }
     if constexpr (DT != 0 && HD == 128) {
-        if constexpr (DT == 1) {     // timing experiments (wrong results), fp16 only
-            if ((p.dbg >> 4) == 1) return launch_mfma<DT, 1>(p, st);
-            if ((p.dbg >> 4) == 2) return launch_mfma<DT, 2>(p, st);
-            if ((p.dbg >> 4) == 32) return launch_mfma<DT, 32>(p, st);
-        }
-        return launch_mfma<DT, 0>(p, st);
+        return launch_mfma<DT>(p, st);
     }
     return APT_ESHAPE;
 }
@@ -1149,12 +1129,6 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     p.n_items = n_items; p.n_hidden_items = n_hidden;
     p.hidden_chunk = rs.s.hidden_chunk; p.kv_chunk = rs.s.kv_chunk; p.items_off = pw[APT_PW_ITEMS_OFF];
     p.scale_log2e = rs.s.softmax_scale * 1.4426950408889634f;
-    {
-        static const int dbg = getenv("APT_DEBUG") ? atoi(getenv("APT_DEBUG")) : 0;
-        static const unsigned long long dbg_buf = getenv("APT_DEBUG_BUF") ? strtoull(getenv("APT_DEBUG_BUF"), nullptr, 0) : 0ull;
-        p.dbg = dbg;
-        p.dbg_buf = (long long*)(uintptr_t)dbg_buf;
-    }
     hipStream_t st = (hipStream_t)stream;
 
     const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;

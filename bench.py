@@ -83,7 +83,7 @@ def main():
                     help="hidden-kind kernel; 'absorbed' is the re-associated form without K/V projection (its "
                          "roofline entry is priced on its own work, never against the MFMA target)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pairs-per-thread", type=int, default=8)
+    ap.add_argument("--pairs-per-thread", type=int, default=48)
     ap.add_argument("--sweep", action="store_true",
                     help="also time hidden-cache ratios 0/25/50/75/100 %% of the same config (adds a 'sweep' list)")
     ap.add_argument("--probe", choices=["copy", "mfma", "sched"], default=None,
@@ -257,14 +257,18 @@ def time_ratio(cfg, ratio, args):
     kms = float(np.mean([ev.elapsed_ms(i) for i in range(args.steps)]))
     ev.close()
     d, e = c.d_model, wl.ELEM_BYTES[c.dtype]
+    absorbed = int(rn.info.hidden_impl) == 3
     flops = 4.0 * d * d * batch.hidden_tokens
-    nbytes = 2.0 * d * e * batch.kv_tokens + 1.0 * d * e * batch.hidden_tokens
+    nbytes = 2.0 * d * e * batch.kv_tokens + (2.0 if absorbed else 1.0) * d * e * batch.hidden_tokens
     del rn, dl, layer
     torch.cuda.empty_cache()
-    return {"hidden_ratio": ratio, "total_tokens": batch.total_tokens, "hidden_tokens": batch.hidden_tokens,
-            "ms_per_step": ms_step, "kernel_ms": kms, "cached_tokens_per_s": batch.total_tokens / (ms_step * 1e-3),
-            "mfma_tflops": flops / (kms * 1e-3) / 1e12, "mfma_frac": flops / (kms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS[c.dtype],
-            "hbm_gbs": nbytes / (kms * 1e-3) / 1e9, "hbm_frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    row = {"hidden_ratio": ratio, "total_tokens": batch.total_tokens, "hidden_tokens": batch.hidden_tokens,
+           "ms_per_step": ms_step, "kernel_ms": kms, "cached_tokens_per_s": batch.total_tokens / (ms_step * 1e-3),
+           "hbm_gbs": nbytes / (kms * 1e-3) / 1e9, "hbm_frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    if not absorbed:        # the absorbed form does no projection: it is never priced in projection flops
+        row.update({"mfma_tflops": flops / (kms * 1e-3) / 1e12,
+                    "mfma_frac": flops / (kms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS[c.dtype]})
+    return row
 
 
 def run_sched_probe(args):

@@ -216,7 +216,7 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
  * weighted sum) like the K and V rows of a KV-kind request, and the two projections shrink to one
  * matrix-vector product per request and head.  Work per hidden token: 4 * d_model * n_heads flops
  * instead of 4 * d_model^2.  Results agree with the other implementations to fp32 rounding.  Needs
- * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 40, and a larger workspace
+ * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 64 (fp32 inputs: <= 40), and a larger workspace
  * (apt_plan_info.workspace_bytes says how much); hidden_chunk must be 0 or 512.
  */
 
@@ -224,7 +224,8 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
  * The same step as apt_hybrid_decode_attn (Eq. 1-3 over both cache kinds); in addition
  * the HIP events ev_begin and ev_end (hipEvent_t handles created by the caller with
  * timing enabled; either may be NULL) are recorded on `stream` immediately before and
- * after the item kernel, so that a caller can time that kernel apart from the merge.
+ * after the item kernel (with APT_HIDDEN_ABSORBED: before the first and after the last of the
+ * kernels that run ahead of the merge), so that a caller can time it apart from the merge.
  */
 int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
                                  const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,

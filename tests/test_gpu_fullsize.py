@@ -71,6 +71,11 @@ def test_opt13b_layer_absorbed_weight_path(oracle):
     _run_and_check(oracle, wl.CONFIGS["opt13b"], n_random=24, hidden_impl=ab.APT_HIDDEN_ABSORBED)
 
 
+def test_opt30b_layer_absorbed_weight_path_56_heads(oracle):
+    from paper_2504_07494_amd import binding as ab
+    _run_and_check(oracle, wl.CONFIGS["opt30b"], n_random=12, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+
+
 def test_opt13b_bf16_all_hidden_absorbed_weight_path(oracle):
     from dataclasses import replace
     from paper_2504_07494_amd import binding as ab

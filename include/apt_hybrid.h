@@ -216,7 +216,7 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
  * weighted sum) like the K and V rows of a KV-kind request, and the two projections shrink to one
  * matrix-vector product per request and head.  Work per hidden token: 4 * d_model * n_heads flops
  * instead of 4 * d_model^2.  Results agree with the other implementations to fp32 rounding.  Needs
- * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 64 (fp32 inputs: <= 40), and a larger workspace
+ * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 128 (fp32 inputs: <= 40), and a larger workspace
  * (apt_plan_info.workspace_bytes says how much); hidden_chunk must be 0 or 512.
  */
 

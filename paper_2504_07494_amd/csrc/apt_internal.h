@@ -85,8 +85,9 @@ static inline apt_ws_layout apt_ws_sections(int64_t n_partials, int H, int hd, i
     if (himpl == APT_HIDDEN_ABSORBED) {
         const uint64_t ks = (uint64_t)(d + APT_ABSORBED_CHUNK - 1) / APT_ABSORBED_CHUNK;
         L.qt = apt_align256(end);
-        // 16-bit inputs: QT is kept as 16-bit parts (2 for fp16, 3 for bf16) of 64 padded heads instead
-        const uint64_t qt_per_elem = dtype == APT_F32 ? (uint64_t)H * 4u : (dtype == APT_F16 ? 256u : 384u);
+        // 16-bit inputs: QT is kept as 16-bit parts (2 for fp16, 3 for bf16) of the heads padded to a multiple of 64 instead
+        const uint64_t head_groups = (uint64_t)(H + 63) / 64;
+        const uint64_t qt_per_elem = dtype == APT_F32 ? (uint64_t)H * 4u : head_groups * (dtype == APT_F16 ? 256u : 384u);
         L.cb = apt_align256(L.qt + (uint64_t)n_hid_req * d * qt_per_elem);
         L.s = apt_align256(L.cb + (uint64_t)n_hid_req * H * 4u);
         L.stat = apt_align256(L.s + ks * (uint64_t)hidden_tokens * H * 4u);

@@ -45,8 +45,8 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
         if (s.hidden_chunk == 0) s.hidden_chunk = APT_MFMA_HIDDEN_CHUNK;
         if (s.hidden_chunk != APT_MFMA_HIDDEN_CHUNK) return APT_ESHAPE;
     } else if (s.hidden_impl == APT_HIDDEN_ABSORBED) {
-        // heads: 64 rows per operand part on the matrix cores (16-bit inputs), 4 x 10 register tiles otherwise
-        const int max_heads = s.dtype == APT_F32 ? APT_ABSORBED_HEAD_GROUPS * APT_ABSORBED_HEADS_PER_THREAD : 64;
+        // heads: groups of 64 rows per operand part on the matrix cores (16-bit inputs), 4 x 10 register tiles otherwise
+        const int max_heads = s.dtype == APT_F32 ? APT_ABSORBED_HEAD_GROUPS * APT_ABSORBED_HEADS_PER_THREAD : 128;
         if (s.d_model % 32 != 0 || s.n_heads > max_heads) return APT_ESHAPE;
         if (s.hidden_chunk == 0) s.hidden_chunk = APT_ABSORBED_CHUNK;
         if (s.hidden_chunk != APT_ABSORBED_CHUNK) return APT_ESHAPE;

@@ -76,6 +76,11 @@ def test_opt30b_layer_absorbed_weight_path_56_heads(oracle):
     _run_and_check(oracle, wl.CONFIGS["opt30b"], n_random=12, hidden_impl=ab.APT_HIDDEN_ABSORBED)
 
 
+def test_opt66b_layer_absorbed_weight_path_72_heads(oracle):
+    from paper_2504_07494_amd import binding as ab
+    _run_and_check(oracle, wl.with_ratio(wl.CONFIGS["opt66b"], 0.5), n_random=10, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+
+
 def test_opt13b_bf16_all_hidden_absorbed_weight_path(oracle):
     from dataclasses import replace
     from paper_2504_07494_amd import binding as ab

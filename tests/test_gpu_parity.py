@@ -101,6 +101,18 @@ def test_absorbed_weight_hidden_path(oracle, dtype, hd, H, bs):
     _check(got, _full(oracle, batch, layer), f"absorbed-{dtype}-hd{hd}", 2e-4, 2e-3)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_absorbed_path_more_than_64_heads(oracle, dtype):
+    # 66 heads: two groups of operand rows, the second with two heads only
+    print(f"[case] absorbed 66 heads {dtype}", flush=True)
+    cfg = wl.small_config(name="absorbed66", dtype=dtype, d_model=66 * 64, n_heads=66, head_dim=64, block_size=16,
+                          batch=4, len_lo=1, len_hi=600, hidden_ratio=0.5)
+    batch = wl.make_batch(cfg, np.array([70, 33, 530, 100], dtype=np.int32), np.array([HID, KV, HID, HID], dtype=np.uint8))
+    layer = wl.make_layer(batch)
+    _, got = _run(batch, layer, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    _check(got, _full(oracle, batch, layer), f"absorbed-66-{dtype}", 2e-4, 2e-3)
+
+
 def test_absorbed_path_many_requests_pure_hidden_and_sixteen_bit_output(oracle):
     # more hidden-kind requests than one pass of the projection kernels holds (16), no KV-kind item
     print("[case] absorbed pure hidden, 19 requests", flush=True)

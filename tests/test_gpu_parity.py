@@ -113,6 +113,17 @@ def test_absorbed_path_more_than_64_heads(oracle, dtype):
     _check(got, _full(oracle, batch, layer), f"absorbed-66-{dtype}", 2e-4, 2e-3)
 
 
+def test_absorbed_path_requests_longer_than_2048_tokens(oracle):
+    # more than 256 runs of 8 tokens per (request, head): the statistics kernel's second and third pass
+    print("[case] absorbed long requests", flush=True)
+    cfg = wl.small_config(name="absorbedlong", dtype="f16", d_model=256, n_heads=2, head_dim=128, block_size=16,
+                          batch=3, len_lo=1, len_hi=4500, hidden_ratio=1.0)
+    batch = wl.make_batch(cfg, np.array([4500, 2049, 10], dtype=np.int32), np.full(3, HID, dtype=np.uint8))
+    layer = wl.make_layer(batch)
+    _, got = _run(batch, layer, hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    _check(got, _full(oracle, batch, layer), "absorbed-long", 2e-4, 2e-3)
+
+
 def test_absorbed_path_many_requests_pure_hidden_and_sixteen_bit_output(oracle):
     # more hidden-kind requests than one pass of the projection kernels holds (16), no KV-kind item
     print("[case] absorbed pure hidden, 19 requests", flush=True)

@@ -42,7 +42,7 @@ enum {
 #define APT_ABSORBED_HEAD_GROUPS 4       // absorbed-weight kernels: threads of a workgroup = 64 x 4 (token or column
 #define APT_ABSORBED_HEADS_PER_THREAD 10 // group, head group), 8 tokens/columns x 10 heads per thread
 #define APT_ABSORBED_CHUNK 512           // = 64 groups x 8 tokens
-#define APT_ABSORBED_OUT_ROWS 128        // d_model rows per partial of the output projection
+#define APT_ABSORBED_OUT_ROWS 256        // d_model rows per partial of the output projection
 
 // per-request arrays of the plan blob, each B words, starting at APT_PW_HEADER
 enum {
@@ -71,7 +71,7 @@ static inline uint64_t apt_align256(uint64_t v) { return (v + 255u) & ~(uint64_t
 // Absorbed-weight hidden path in addition (fp32), with KS = ceil(d / 512) slices of d_model: absorbed queries
 // QT [n_hid_req][H][d] (16-bit inputs: [n_hid_req][d / 32][parts * 64][32] 16-bit parts), score offsets CB [n_hid_req][H], score partials S [KS][H][hidden_tokens] (slice 0 then
 // holds the scores), statistics ML [n_hid_req][H] (m, l), the partial weighted sums YP [n_hidden_chunks][H][d]
-// the output partials OP [ceil(d / 128)][n_hid_req][H][hd], and (16-bit inputs) the softmax weights PP as 16-bit parts.
+// the output partials OP [ceil(d / 256)][n_hid_req][H][hd], and (16-bit inputs) the softmax weights PP as 16-bit parts.
 struct apt_ws_layout {
     uint64_t acc, ml, qt, cb, s, stat, yp, op, pp, total;
 };

@@ -97,7 +97,7 @@ def test_absorbed_plan_has_one_hidden_item_per_range_and_the_request_maps():
     H, d, nh = 40, 5120, len(hid)
     end = want["n_partials"] * H * (128 + 2) * 4
     ks = d // 512
-    for sec in (nh * d * 256, nh * H * 4, ks * tok * H * 4, nh * H * 8, chunk * H * d * 4, (d // 128) * nh * H * 128 * 4):
+    for sec in (nh * d * 256, nh * H * 4, ks * tok * H * 4, nh * H * 8, chunk * H * d * 4, (d // 256) * nh * H * 128 * 4):
         end = al(end) + sec
     assert info.workspace_bytes == al(end) + chunk * 16 * 32 * 256
     for bad in (dict(n_heads=129, d_model=129 * 128), dict(n_heads=41, d_model=41 * 128, dtype="f32"), dict(hidden_chunk=256)):

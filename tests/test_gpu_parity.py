@@ -150,6 +150,18 @@ def test_mfma_and_valu_hidden_kernels_agree(oracle):
     assert np.max(np.abs(a - b)) < 1e-4
 
 
+@pytest.mark.parametrize("impl", [ab.APT_HIDDEN_AUTO, ab.APT_HIDDEN_ABSORBED])
+def test_long_contexts_many_ranges_per_request(oracle, impl):
+    # 16k-token requests: 64 hidden ranges / 32 KV ranges per (request, head) to merge
+    print(f"[case] long contexts hidden_impl={impl}", flush=True)
+    cfg = wl.small_config(name="long", dtype="bf16", d_model=256, n_heads=2, head_dim=128, block_size=16,
+                          batch=4, len_lo=1, len_hi=16384, hidden_ratio=0.5)
+    batch = wl.make_batch(cfg, np.array([16384, 16383, 9000, 5], dtype=np.int32), np.array([HID, KV, HID, KV], dtype=np.uint8))
+    layer = wl.make_layer(batch)
+    rn, got = _run(batch, layer, hidden_impl=impl)
+    _check(got, _full(oracle, batch, layer), f"long-{impl}", 2e-4, 2e-3)
+
+
 @pytest.mark.parametrize("kinds", ["all_kv", "all_hidden"])
 def test_pure_batches_and_single_request(oracle, kinds):
     print(f"[case] pure {kinds}", flush=True)

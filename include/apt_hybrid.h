@@ -21,10 +21,11 @@
  *     (APT_OK) or a negative apt_status; apt_strerror() names it.
  *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
  *     memory of the current device.  The caller owns every buffer.  The library
- *     allocates no device memory and keeps no state between calls.
+ *     allocates no device memory and keeps no state between calls (apt_pool_* keep
+ *     their state in the host handle the caller holds; apt_schedule is a pure function).
  *   - Launching functions take a HIP stream as void* (NULL = default stream) and
  *     return after enqueueing; inputs are read-only, only `out`, `workspace`,
- *     `packed` (apt_pack_weights), the cache pools (apt_cache_append) and one
+ *     `packed` (apt_pack_weights), the cache pools (apt_cache_append, apt_cache_write) and one
  *     counter word of `plan_dev` are written.
  *   - Arguments are validated on the host before anything is launched.  Block
  *     ids inside block_tables are NOT range-checked on the device; use
@@ -143,8 +144,8 @@ int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
  * the shorter last ranges by decreasing length (ties by request, head); then the KV kind by
  * decreasing range length (ties by request, range, head).  With APT_HIDDEN_ABSORBED a hidden-kind
  * item covers all heads of its range: one item (request, 0, t0, t1) per range, all in queue 0, by
- * request and range.  The order only steers which
- * workgroup takes which item (cache locality, balance); every item is independent.
+ * request and range.  The order only steers which workgroup takes which item (cache locality,
+ * balance); every item is independent.
  * Integer-only; the same inputs always give the same bytes.
  * Errors: APT_EINVAL (null, B < 1, length < 1, unknown kind), APT_ERANGE (length
  * beyond max_blocks_per_req*block_size), APT_EWORKSPACE (plan_bytes too small),

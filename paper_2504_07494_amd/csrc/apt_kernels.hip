@@ -8,6 +8,8 @@
 //                                      for fp32) and attends to them from registers
 //                  every item writes one partial (m, l, acc[head_dim]) in fp32
 //   merge kernel   combines a request's partials per head and normalises
+//   apt_absorbed.inc: the hidden-kind requests without the projection (opt-in, APT_HIDDEN_ABSORBED)
+//   cache append / cache write, weight packing, calibration kernels
 //
 // Scores are kept in base-2 units: s2 = softmax_scale*log2(e)*<q,k>, weights 2^(s2 - m).
 #include <hip/hip_runtime.h>

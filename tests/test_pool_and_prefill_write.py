@@ -150,6 +150,34 @@ def _rows(cfg, n, seed):
     return x, k, v
 
 
+def test_oracle_range_write_puts_the_papers_example_prompts_in_place(oracle):
+    # Section 4.3 example, block size 4: request A (KV cache, 7 prompt tokens) has K blocks 0, 2 and
+    # V blocks 8, 10 for its prompt; request B (hidden cache, 6 prompt tokens) has blocks 5, 7.
+    # After the prefill's write position j sits in block list entry j // 4 at slot j % 4.
+    ex = _read_pool_example()
+    bs, d, H, hd = ex["block_size"], 8, 2, 4
+    bt = np.full((2, 2, 4), -1, dtype=np.int32)
+    bt[0, 0, :3] = ex["A"]["k_blocks"]; bt[0, 1, :3] = ex["A"]["v_blocks"]; bt[1, 0, :4] = ex["B"]["h_blocks"]
+    ctx = np.array([7, 6], dtype=np.int32)                     # prompt lengths: everything is new
+    kinds = np.array([KV, HID], dtype=np.uint8)
+    off = np.array([0, 7, 13], dtype=np.int32)
+    rows = 13
+    x = (np.arange(rows * d, dtype=np.float32).reshape(rows, d) + 1000)
+    k = (np.arange(rows * d, dtype=np.float32).reshape(rows, H, hd) + 2000)
+    v = (np.arange(rows * d, dtype=np.float32).reshape(rows, H, hd) + 3000)
+    pool = np.zeros((ex["pool_blocks"], bs * d), dtype=np.float32)
+    oracle.write(oracle.shape_of(d, H, hd, bs, "f32", 4, 1.0), off, x, k, v, pool, pool, pool, bt, ctx, kinds)
+    want = np.zeros_like(pool)
+    for j in range(7):                                         # A: rows 0..6
+        kb, vb = ex["A"]["k_blocks"][j // bs], ex["A"]["v_blocks"][j // bs]
+        want[kb].reshape(H, bs, hd)[:, j % bs, :] = k[j]
+        want[vb].reshape(H, bs, hd)[:, j % bs, :] = v[j]
+    for j in range(6):                                         # B: rows 7..12
+        want[ex["B"]["h_blocks"][j // bs]].reshape(bs, d)[j % bs, :] = x[7 + j]
+    assert np.array_equal(pool, want)
+    assert set(np.nonzero(pool.any(axis=1))[0]) == {0, 2, 8, 10, 5, 7}
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_oracle_range_write_equals_repeated_single_token_appends(oracle, dtype):
     # a run of n_r tokens written at once = n_r appends with growing lengths (the single-token

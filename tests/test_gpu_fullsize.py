@@ -62,6 +62,29 @@ def test_opt13b_layer(oracle):
     _run_and_check(oracle, wl.CONFIGS["opt13b"], n_random=24)
 
 
+@pytest.mark.timeout(600)
+def test_opt13b_layer_every_request_and_head(oracle):
+    """The bench workload element by element: all 64 x 40 (request, head) outputs of both hidden paths
+    against the oracle (about half a minute of oracle time on 16 host threads)."""
+    from paper_2504_07494_amd import binding as ab
+    from paper_2504_07494_amd.harness import DecodeRunner
+    cfg = wl.CONFIGS["opt13b"]
+    print(f"[case] full size {cfg.name}, every (request, head)", flush=True)
+    batch = wl.make_batch(cfg)
+    layer = wl.make_layer(batch, workers=16)
+    want = oracle_attn(oracle, batch, layer).reshape(batch.B, cfg.n_heads, cfg.head_dim)
+    for impl in (ab.APT_HIDDEN_AUTO, ab.APT_HIDDEN_ABSORBED):
+        rn = DecodeRunner(batch, hidden_impl=impl)
+        rn.run(rn.upload(layer))
+        got = rn.out_f64()
+        err = np.abs(got - want)
+        big = np.abs(want) >= 1e-2
+        a, r = float(err.max()), float((err[big] / np.abs(want[big])).max())
+        print(f"[parity] {cfg.name} all pairs, hidden_impl={impl}: max_abs={a:.3e} max_rel={r:.3e}", flush=True)
+        assert np.all(np.isfinite(got)) and a <= 2e-3 and r <= 1e-2
+        del rn
+
+
 def test_opt30b_layer_permuted_pages(oracle):
     _run_and_check(oracle, wl.CONFIGS["opt30b"], n_random=16)
 

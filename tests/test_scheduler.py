@@ -88,3 +88,59 @@ def test_c_abi_rejects_bad_arguments_and_is_fast_enough():
     ms = (time.perf_counter() - t) / 20 * 1e3
     print(f"apt_schedule, 1600 candidates: {ms:.3f} ms")
     assert ms < 10.8
+
+
+def test_schedule_and_pool_compose_admitted_requests_always_fit_and_can_grow():
+    """Prefill iterations of a small serving simulation: the candidates are the waiting requests, the
+    memory constraint is the pool size minus the maximum requirement of the running requests
+    (Section 5, after Definition 1), m_i is a request's KV blocks at its maximum length.  Whatever the
+    greedy schedule admits can then be assigned in the pool in the kind it chose and extended to its
+    maximum length without ever running out of blocks."""
+    g = np.random.default_rng(9)
+    n_blocks, bs, mb, nslots = 400, 16, 16, 24
+    pool = ab.apt_pool_create(n_blocks, bs, mb, nslots)
+    waiting, running, t = [], {}, 0.0            # waiting: (arrival time, prompt, max_len); running: slot -> dict
+    rho = 2e-4
+    admitted_hidden = admitted_kv = 0
+    try:
+        for it in range(300):
+            t += 0.05
+            for _ in range(g.poisson(0.7)):
+                prompt = int(g.integers(1, 120))
+                waiting.append((t, prompt, min(mb * bs, prompt + int(g.integers(1, 120)))))
+            # decode progress and departures
+            for slot in list(running):
+                r = running[slot]
+                if r["len"] < r["max_len"]:
+                    r["len"] += 1
+                    ab.apt_pool_extend(pool, slot, r["len"])      # never APT_EFULL: the growth was reserved
+                else:
+                    ab.apt_pool_release(pool, slot)
+                    del running[slot]
+            free_slots = [s for s in range(nslots) if s not in running]
+            if not waiting or not free_slots:
+                continue
+            cand = waiting[:len(free_slots)]
+            pending = np.array([t - a for a, _, _ in cand], dtype=np.float64)
+            mem = np.array([2 * -(-m // bs) for _, _, m in cand], dtype=np.int64)
+            reserved = sum((2 if r["kind"] == 0 else 1) * -(-r["max_len"] // bs) for r in running.values())
+            limit = n_blocks - reserved
+            alpha, beta, _ = ab.apt_schedule(pending, mem, max(limit, 0), len(waiting) + len(running), rho)
+            used = sum(int(m) // (2 if b else 1) for m, a, b in zip(mem, alpha, beta) if a)
+            assert used <= max(limit, 0)
+            keep = []
+            for (arr, prompt, max_len), a, b in zip(cand, alpha, beta):
+                if not a:
+                    keep.append((arr, prompt, max_len))
+                    continue
+                slot = free_slots.pop(0)
+                kind = 1 if b else 0
+                ab.apt_pool_assign(pool, slot, kind, prompt)       # never APT_EFULL
+                running[slot] = {"kind": kind, "len": prompt, "max_len": max_len}
+                admitted_hidden += int(b)
+                admitted_kv += int(not b)
+            waiting = keep + waiting[len(cand):]
+            assert ab.apt_pool_free_blocks(pool) >= 0
+        assert admitted_hidden > 0 and admitted_kv > 0          # the simulation exercised both cache kinds
+    finally:
+        ab.apt_pool_destroy(pool)

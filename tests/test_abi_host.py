@@ -168,3 +168,25 @@ def test_attention_call_rejects_bad_arguments_before_any_launch():
     with pytest.raises(ab.AptError) as e:
         ab.apt_hybrid_decode_attn(shape, buf, 16, 16, 16, 16, None, None, None, None, None, None, 16, 16, 16, 8)
     assert e.value.status == ab.APT_EWORKSPACE
+
+
+def test_cache_write_calls_reject_bad_arguments_before_any_launch():
+    shape = _shape()
+    P = 16          # any non-null address: validation fails before a launch could use it
+    for call in (lambda: ab.apt_cache_append(shape, 0, P, None, None, None, None, P, P, P, P),            # B < 1
+                 lambda: ab.apt_cache_append(shape, 2, None, None, None, P, P, P, P, P, P),                # nothing to write
+                 lambda: ab.apt_cache_append(shape, 2, P, None, None, None, None, None, P, P, P),          # x without its pool
+                 lambda: ab.apt_cache_append(shape, 2, None, P, None, P, P, None, P, P, P),                # k without v
+                 lambda: ab.apt_cache_append(shape, 2, None, P, P, P, None, None, P, P, P),                # v pool missing
+                 lambda: ab.apt_cache_write(shape, 2, None, 4, P, None, None, None, None, P, P, P, P),     # no offsets
+                 lambda: ab.apt_cache_write(shape, 2, P, 0, P, None, None, None, None, P, P, P, P),        # max_new_tokens < 1
+                 lambda: ab.apt_cache_write(shape, 2, P, 4, P, None, None, None, None, P, None, P, P)):    # no block tables
+        with pytest.raises(ab.AptError) as e:
+            call()
+        assert e.value.status == ab.APT_EINVAL
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_cache_write(shape, 2, P, 8 * 65536, P, None, None, None, None, P, P, P, P)
+    assert e.value.status == ab.APT_ERANGE
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_cache_write(_shape(head_dim=96, d_model=96 * 40), 2, P, 4, P, None, None, None, None, P, P, P, P)
+    assert e.value.status == ab.APT_ESHAPE

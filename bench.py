@@ -83,6 +83,9 @@ def main():
                     help="hidden-kind kernel; 'absorbed' is the re-associated form without K/V projection (its "
                          "roofline entry is priced on its own work, never against the MFMA target)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="skip the short extra measurement of the absorbed-weight hidden path (single-layer runs "
+                         "of the default hidden path add it under 'next_rows'; it never enters 'value')")
     ap.add_argument("--pairs-per-thread", type=int, default=48)
     ap.add_argument("--sweep", action="store_true",
                     help="also time hidden-cache ratios 0/25/50/75/100 %% of the same config (adds a 'sweep' list)")
@@ -215,6 +218,27 @@ def main():
         }
         result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
                                    "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
+    if nl == 1 and himpl == 0 and hidden_tokens > 0 and not args.no_next_rows and not args.sweep:
+        # context only: the same step with hidden-kind requests through the absorbed-weight form (no K/V
+        # projection: not the paper's method, so it is never the headline and never priced in projection flops)
+        rn2 = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=3)
+        dl2 = rn2.upload(layer)
+        for _ in range(3):
+            rn2.plan()
+            rn2.run(dl2)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(args.steps):
+            rn2.plan()
+            rn2.run(dl2)
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
+        dev = float((rn2.out.float() - rn.out.float()).abs().max())
+        result["next_rows"] = {"absorbed_weight_hidden_path": {
+            "ms_per_step": ms2, "cached_tokens_per_s": total_tokens / (ms2 * 1e-3),
+            "max_abs_difference_to_default_path": dev,
+            "hbm_frac_on_own_bytes": (kv_bytes + 2.0 * d * e * hidden_tokens) / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS}}
+        del rn2, dl2
     if args.sweep:
         del rn, dls, dl
         torch.cuda.empty_cache()

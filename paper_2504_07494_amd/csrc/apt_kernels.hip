@@ -424,17 +424,20 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     // b_row + i * b_step, in the W image (K: A side, V: B side) or the X image.  Unit of
     // sub-step ks: (2 ks + half) ^ swz(row), so its address is the ks = 0 address ^ (32 ks);
     // swz does not change with the slot (row steps of 32 and 64).
+    // (computed per item, right before its k loop: kept across the epilogue they would sit in scratch)
     uint32_t a_addr[4], b_addr[4];
-    {
-        const int wrow = mat * 128 + (lane & 31), xrow = th * 32 + (lane & 31);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int wr = wrow + 32 * i, xr = xrow + 64 * i;
-            const uint32_t wa = lds_base + wr * kRowBytes + ((half ^ swz(wr)) * 16);
-            const uint32_t xa = lds_base + kStages * kTileBytes + xr * kRowBytes + ((half ^ swz(xr)) * 16);
-            a_addr[i] = mat == 0 ? wa : xa;
-            b_addr[i] = mat == 0 ? xa : wa;
-        }
+#define APT_OPERAND_ADDRESSES()                                                                             \
+    {                                                                                                       \
+        int ln_ = lane, hf_ = half;                                                                         \
+        asm volatile("" : "+v"(ln_), "+v"(hf_));                                                            \
+        const int wrow_ = mat * 128 + (ln_ & 31), xrow_ = th * 32 + (ln_ & 31);                             \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
+            const int wr_ = wrow_ + 32 * i_, xr_ = xrow_ + 64 * i_;                                         \
+            const uint32_t wa_ = lds_base + wr_ * kRowBytes + ((hf_ ^ swz(wr_)) * 16);                      \
+            const uint32_t xa_ = lds_base + kStages * kTileBytes + xr_ * kRowBytes + ((hf_ ^ swz(xr_)) * 16); \
+            a_addr[i_] = mat == 0 ? wa_ : xa_;                                                              \
+            b_addr[i_] = mat == 0 ? xa_ : wa_;                                                              \
+        }                                                                                                   \
     }
 
     // ---- this workgroup's share of the hidden-kind items
@@ -597,6 +600,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+        APT_OPERAND_ADDRESSES()
         // everything issued so far has to land here: the loads the compiler keeps track of (or the
         // wait counts it would place inside the k loop for them would also wait for the staging
         // copies) and with them the first three k-tiles
@@ -628,6 +632,10 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 
         // ---- epilogue.  Register e of tile (i, j): row 8 (e/4) + 4 half + e%4 of the A-side
         // block i, column lane%32 of the B-side block j.
+        // lane-dependent LDS addresses of the epilogue are rebuilt here from values the compiler cannot see
+        // through: hoisted out of the item loop they would stay live across the k loops and end up in scratch
+        int ln = lane, hf = half, td = tid;
+        asm volatile("" : "+v"(ln), "+v"(hf), "+v"(td));
         if (mat == 0) {
             // K wave: rows = channels 32 i + ..., columns = tokens of block 2 j + th
             const float qb = ml_lds[4] + ml_lds[5];
@@ -636,7 +644,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
-                    const float4 q4 = *(const float4*)(qs_lds + 32 * i + 8 * e4 + 4 * half);
+                    const float4 q4 = *(const float4*)(qs_lds + 32 * i + 8 * e4 + 4 * hf);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         sp[j] = fmaf(acc[i][j][4 * e4 + 0], q4.x, sp[j]);
@@ -644,13 +652,17 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
                         sp[j] = fmaf(acc[i][j][4 * e4 + 2], q4.z, sp[j]);
                         sp[j] = fmaf(acc[i][j][4 * e4 + 3], q4.w, sp[j]);
                     }
+                    // the accumulators are read out of the AGPRs in small groups: read all at once they
+                    // push every long-lived value into scratch, and a scratch reload waits for the copies
+                    // of the next item's k-tiles that are in flight here
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             float m = kSentinel;
             bool ok[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 sp[j] += __shfl_xor(sp[j], 32);
-                ok[j] = (2 * j + th) * 32 + (lane & 31) < nvalid;
+                ok[j] = (2 * j + th) * 32 + (ln & 31) < nvalid;
                 sp[j] = ok[j] ? sp[j] + qb : kSentinel;
                 m = fmaxf(m, sp[j]);
             }
@@ -660,10 +672,10 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             for (int j = 0; j < 4; ++j) {
                 const float pw = ok[j] ? fast_exp2(sp[j] - m) : 0.f;
                 l += pw;
-                if (lane < 32) p_lds[(2 * j + th) * 32 + lane] = pw;
+                if (ln < 32) p_lds[(2 * j + th) * 32 + ln] = pw;
             }
             l = group_sum<32>(l);
-            if (lane == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
+            if (ln == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
         }
         __syncthreads();
         if (have_next) APT_STAGE_FIRST(3, 4)      // every wave has left the k loop: stage 3 is free too
@@ -674,7 +686,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
-                    const float4 p4 = *(const float4*)(p_lds + (2 * i + th) * 32 + 8 * e4 + 4 * half);
+                    const float4 p4 = *(const float4*)(p_lds + (2 * i + th) * 32 + 8 * e4 + 4 * hf);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         o[j] = fmaf(acc[i][j][4 * e4 + 0], p4.x, o[j]);
@@ -682,22 +694,23 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
                         o[j] = fmaf(acc[i][j][4 * e4 + 2], p4.z, o[j]);
                         o[j] = fmaf(acc[i][j][4 * e4 + 3], p4.w, o[j]);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             const float l = ml_lds[th * 2 + 1];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 o[j] += __shfl_xor(o[j], 32);
-                if (lane < 32) o_lds[th * 128 + 32 * j + lane] = fmaf(l, bv_lds[32 * j + lane], o[j]);
+                if (ln < 32) o_lds[th * 128 + 32 * j + ln] = fmaf(l, bv_lds[32 * j + ln], o[j]);
             }
         }
         __syncthreads();
-        if (tid < HD) {
+        if (td < HD) {
             const float m0 = ml_lds[0], l0 = ml_lds[1], m1 = ml_lds[2], l1 = ml_lds[3];
             const float M = fmaxf(m0, m1);
             const float w0 = fast_exp2(m0 - M), w1 = fast_exp2(m1 - M);
             const int64_t slot = ((int64_t)ws_offset[r] + t0 / p.hidden_chunk) * p.H + h;
-            p.ws_acc[slot * HD + tid] = o_lds[tid] * w0 + o_lds[128 + tid] * w1;
-            if (tid == 0) p.ws_ml[slot] = make_float2(M, l0 * w0 + l1 * w1);
+            p.ws_acc[slot * HD + td] = o_lds[td] * w0 + o_lds[128 + td] * w1;
+            if (td == 0) p.ws_ml[slot] = make_float2(M, l0 * w0 + l1 * w1);
         }
         have = have_next;
         qi = nqi;
@@ -709,6 +722,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #undef APT_MFMA_ALL
 #undef APT_LOAD_FRAGS
 #undef APT_STAGE_FIRST
+#undef APT_OPERAND_ADDRESSES
 #undef APT_MAKE_SOURCES
 
     // ---- then a share of the KV-kind items, longest first

@@ -21,7 +21,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # APT_ORACLE_LIB: a test loads a deliberately altered build of the oracle (mutation check of the pins)
+        path = os.environ.get("APT_ORACLE_LIB") or _build.build(force=False)
         _lib = C.CDLL(path)
         _lib.apt_oracle_threads.restype = C.c_int
         for name in ("apt_oracle_attn", "apt_oracle_partial", "apt_oracle_merge", "apt_oracle_append"):

@@ -1,7 +1,10 @@
-"""Greedy solution of the hybrid-cache scheduling problem (Section 5, Definition 1).  The rule is
-pinned against the problem's definition by exhaustive search on tiny instances (feasible, and at
-least half of the optimum) and by cases whose answer is known; the C ABI is compared with the
-rule decision by decision."""
+"""Greedy solution of the hybrid-cache scheduling problem (Section 5, Definition 1).  The rule
+(oracle/sched_oracle.greedy: the paper's state-by-state marginal-gain process, written without a
+candidate list or a sort) is pinned against the problem's definition by exhaustive search on tiny
+instances (feasible, and at least half of the optimum) and by cases whose answer is known.  The C
+ABI is checked the same way against Definition 1 directly (feasible, >= half of the exhaustive
+optimum, objective equals the definition's value of its decisions, invariance under rescaling of
+time), and decision by decision against the rule."""
 import time
 
 import numpy as np
@@ -55,6 +58,24 @@ def test_known_cases():
     # the single valuable request beats the dense small ones: density order alone would take request 0 first
     a, b, v = so.greedy([1.0, 50.0], [2, 200], 200, 2, 10.0)
     assert a == [0, 1] and b == [0, 0] and v == 50.0
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_c_abi_against_definition_1_directly(seed):
+    g = np.random.default_rng(50 + seed)
+    for _ in range(40):
+        n = int(g.integers(1, 8))
+        pending, mem, limit = _instance(g, n, g.choice([0.1, 0.3, 0.5, 0.8, 1.2]))
+        n_unf, rho = int(g.integers(1, 60)), float(g.choice([0.0, 1e-5, 1e-4, 1e-3, 1e-2]))
+        alpha, beta, val = ab.apt_schedule(pending, mem, limit, n_unf, rho)
+        got_val, used = so.value_and_memory(pending, mem, n_unf, rho, alpha.tolist(), beta.tolist())
+        assert used <= limit and all(b <= a for a, b in zip(alpha, beta))
+        assert abs(got_val - val) <= 1e-9 * max(1.0, abs(val))
+        opt = so.optimum(pending.tolist(), mem.tolist(), limit, n_unf, rho)
+        assert 0.5 * opt - 1e-12 <= val <= opt + 1e-9, (val, opt)
+        # time measured in another unit (pending times and rho scaled by a power of two): same decisions
+        a2, b2, v2 = ab.apt_schedule(pending * 4.0, mem, limit, n_unf, rho * 4.0)
+        assert a2.tolist() == alpha.tolist() and b2.tolist() == beta.tolist() and abs(v2 - 4.0 * val) <= 1e-9 * max(1.0, v2)
 
 
 @pytest.mark.parametrize("seed,n", [(0, 1), (1, 7), (2, 50), (3, 400), (4, 1600)])

@@ -1,13 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the hybrid-cache decode attention step on one MI355X.
 
-    python bench.py --gpus 1 --steps K --warmup W [--config opt13b] [--hidden-ratio R]
+    python bench.py --gpus 1 --steps K --warmup W [--config opt66b] [--hidden-ratio R]
 
 A step is one pass of the whole hot path for one layer over one synthetic batch whose
 inputs are already resident in HBM: the ragged work partition (host planner + copy of the
 plan to the device), the item kernel (paged-KV attention and hidden-cache recompute +
 attention in one launch) and the merge kernel.  The metric is cached tokens per second
 per decode layer = sum of the batch's context lengths / time per step.
+
+Default run (no flags): the OPT-66B-shaped layer (batch 256), the largest single-layer
+configuration.  The headline `value`, `roofline` and `cpu_baseline` are its 50 % hidden-cache
+point; `sweep` holds the hidden-cache ratios 0/25/50/75/100 % of the same batch (0 % is the
+HBM-bound point, 100 % the MFMA-bound one), each timed with the same W warm-up and K timed
+steps; `rho_fit` is the least-squares line of the item-kernel time over the hidden tokens
+(Section 4.2, Eq. 5-6: t = rho * m); `other_configs` adds the OPT-13B- and OPT-30B-shaped
+layers and the 40-layer OPT-13B-shaped step (--no-extras skips them).
 
 Prints ONE JSON line.  `roofline` describes the item kernel, timed with HIP events
 recorded around it on its launch stream inside the timed region.  `cpu_baseline` is the
@@ -29,6 +37,8 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
+# the absorbed-weight hidden path (opt-in, not the paper's method) reads every cached hidden row twice
+ABSORBED_X_READS = 2.0
 
 
 class HipEvents:
@@ -71,12 +81,125 @@ def read_traffic(workload_key):
     return None
 
 
+HIMPL = {"auto": 0, "valu": 1, "mfma": 2, "absorbed": 3}
+
+
+def measure(cfg, args, steps, warmup, keep=False):
+    """W warm-up steps, then K timed steps (plan + plan copy + one attention call per layer) of one workload,
+    bracketed by device synchronisations.  Returns a dict of the measured numbers; with keep=True also the
+    runner, the batch and the last layer's host copy (for the oracle sample)."""
+    import numpy as np
+    import torch
+    from paper_2504_07494_amd import workloads as wl
+    from paper_2504_07494_amd.harness import DecodeRunner
+
+    t_gen = time.time()
+    batch = wl.make_batch(cfg)
+    nl = cfg.n_layers
+    himpl = HIMPL[args.hidden_impl]
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=himpl)
+    layer, dls = None, []
+    for li in range(nl):                      # every layer of the step is resident in HBM
+        layer = wl.make_layer(batch, layer=li, workers=min(16, os.cpu_count() or 8))
+        dls.append(rn.upload(layer, keep_raw_weights=(nl == 1 or himpl == 3)))
+    t_gen = time.time() - t_gen
+    torch.cuda.synchronize()
+
+    for _ in range(warmup):
+        rn.run_step(dls)
+    torch.cuda.synchronize()
+
+    ev = HipEvents(steps * nl)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        rn.plan()
+        for li in range(nl):
+            rn.run(dls[li], ev.pairs[i * nl + li][0], ev.pairs[i * nl + li][1])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    kern_ms = [ev.elapsed_ms(i) for i in range(steps * nl)]
+    ev.close()
+    kern_avg_ms = float(np.mean(kern_ms))
+
+    total_tokens, hidden_tokens, kv_tokens = batch.total_tokens, batch.hidden_tokens, batch.kv_tokens
+    d, e = cfg.d_model, wl.ELEM_BYTES[cfg.dtype]
+    # algorithmic work of the item kernel per launch
+    flops = 4.0 * d * d * hidden_tokens                 # K and V projections of hidden-kind tokens
+    kv_bytes = 2.0 * d * e * kv_tokens                  # K row + V row of KV-kind tokens
+    hid_bytes = 1.0 * d * e * hidden_tokens
+    absorbed = int(rn.info.hidden_impl) == 3 and hidden_tokens > 0
+    if absorbed:
+        # absorbed form: no projection; per hidden token and head one d_model-long dot product and one
+        # d_model-long weighted row update (4 d H flops); priced against HBM, on its own bytes
+        flops = 4.0 * d * cfg.n_heads * hidden_tokens
+        hid_bytes = ABSORBED_X_READS * d * e * hidden_tokens
+    t_mfma = flops / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)
+    t_hbm = (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
+    wkey = f"{cfg.name}@{cfg.hidden_ratio:g}" + ("@absorbed" if absorbed else "")
+    tflops = flops / (kern_avg_ms * 1e-3) / 1e12
+    gbs = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
+    if not absorbed and t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_MFMA_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
+                "frac": tflops / PEAK_MFMA_TFLOPS[cfg.dtype], "traffic": read_traffic(wkey)}
+    else:
+        roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": gbs / PEAK_HBM_GBS, "traffic": read_traffic(wkey)}
+    mfma_items = rn.info.n_hidden_items > 0 and rn.info.hidden_impl == 2
+    kname = "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel"
+    if absorbed:
+        kname = "apt_absorb_{q,score,stats,pv,out,final}_kernel + apt_items_kernel (one event pair around all of them)"
+    roof.update({"kernel": kname, "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
+                 "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
+    m = {
+        # cached tokens per second per decode layer: a step of nl layers serves total_tokens in each layer
+        "value": total_tokens * nl / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "roofline": roof,
+        "workload": f"{cfg.name}: d_model={d}, {cfg.n_heads} heads x {cfg.head_dim}, {cfg.dtype}, "
+                    f"batch {batch.B}, ctx {cfg.len_dist}[{cfg.len_lo},{cfg.len_hi}], block {cfg.block_size}, "
+                    f"{int(round(100 * cfg.hidden_ratio))}% hidden-cache requests"
+                    + (f", {nl} layers per step (one plan, {nl} attention calls)" if nl > 1 else ""),
+        "config": {"layers_per_step": nl, "total_tokens": total_tokens, "hidden_tokens": hidden_tokens,
+                   "kv_tokens": kv_tokens,
+                   "hidden_impl": {1: "valu", 2: "mfma", 3: "absorbed"}[int(rn.info.hidden_impl)],
+                   "n_items": int(rn.info.n_items), "n_hidden_items": int(rn.info.n_hidden_items),
+                   "seed": cfg.seed, "input_gen_s": round(t_gen, 2)},
+        "mfma_frac": None if absorbed else tflops / PEAK_MFMA_TFLOPS[cfg.dtype],
+        "hbm_frac": gbs / PEAK_HBM_GBS, "dtype": cfg.dtype,
+    }
+    if keep:
+        m["_keep"] = (rn, batch, layer, dls)
+    else:
+        del rn, dls, layer
+        torch.cuda.empty_cache()
+    return m
+
+
+def sweep_row(ratio, m):
+    r = m["roofline"]
+    row = {"hidden_ratio": ratio, "total_tokens": m["config"]["total_tokens"], "hidden_tokens": m["config"]["hidden_tokens"],
+           "ms_per_step": m["ms_per_step"], "kernel_ms": r["kernel_ms"], "cached_tokens_per_s": m["value"],
+           "bound": r["bound"], "hbm_gbs": m["hbm_frac"] * PEAK_HBM_GBS, "hbm_frac": m["hbm_frac"]}
+    if m["mfma_frac"] is not None:        # the absorbed form does no projection: never priced in projection flops
+        row.update({"mfma_tflops": m["mfma_frac"] * PEAK_MFMA_TFLOPS[m["dtype"]], "mfma_frac": m["mfma_frac"]})
+    return row
+
+
+def brief(m):
+    r = m["roofline"]
+    return {"workload": m["workload"], "cached_tokens_per_s": m["value"], "ms_per_step": m["ms_per_step"],
+            "kernel_ms": r["kernel_ms"], "bound": r["bound"], "roofline_frac": r["frac"], "mfma_frac": m["mfma_frac"],
+            "hbm_frac": m["hbm_frac"], "total_tokens": m["config"]["total_tokens"],
+            "hidden_tokens": m["config"]["hidden_tokens"], "layers_per_step": m["config"]["layers_per_step"],
+            "input_gen_s": m["config"]["input_gen_s"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="opt13b")
+    ap.add_argument("--config", default="opt66b")
     ap.add_argument("--hidden-ratio", type=float, default=None)
     ap.add_argument("--kv-chunk", type=int, default=0)
     ap.add_argument("--hidden-impl", choices=["auto", "valu", "mfma", "absorbed"], default="auto",
@@ -87,8 +210,12 @@ def main():
                     help="skip the short extra measurement of the absorbed-weight hidden path (single-layer runs "
                          "of the default hidden path add it under 'next_rows'; it never enters 'value')")
     ap.add_argument("--pairs-per-thread", type=int, default=48)
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time hidden-cache ratios 0/25/50/75/100 %% of the same config (adds a 'sweep' list)")
+    ap.add_argument("--sweep", dest="sweep", action="store_true", default=None,
+                    help="time hidden-cache ratios 0/25/50/75/100 %% of the config (adds 'sweep' and 'rho_fit'); "
+                         "on by default for the default config when no --hidden-ratio is given")
+    ap.add_argument("--no-sweep", dest="sweep", action="store_false")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other configurations (opt13b, opt30b, the 40-layer opt13b_step) of the default run")
     ap.add_argument("--probe", choices=["copy", "mfma", "sched"], default=None,
                     help="run only a calibration kernel (plain copy of 1 GiB, or the register-only MFMA loop), or time "
                          "the host-side greedy scheduler at the candidate counts of the paper's scalability table")
@@ -106,92 +233,40 @@ def main():
     if args.probe:
         return run_probe(args)
 
+    default_run = args.config == "opt66b" and args.hidden_ratio is None and args.hidden_impl == "auto"
+    do_sweep = args.sweep if args.sweep is not None else default_run
+    do_extras = default_run and not args.no_extras
     cfg = wl.CONFIGS[args.config]
     if args.hidden_ratio is not None:
         cfg = wl.with_ratio(cfg, args.hidden_ratio)
-    t_gen = time.time()
-    batch = wl.make_batch(cfg)
     nl = cfg.n_layers
-    himpl = {"auto": 0, "valu": 1, "mfma": 2, "absorbed": 3}[args.hidden_impl]
-    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=himpl)
-    layer, dls = None, []
-    for li in range(nl):                      # every layer of the step is resident in HBM
-        layer = wl.make_layer(batch, layer=li, workers=min(16, os.cpu_count() or 8))
-        dls.append(rn.upload(layer, keep_raw_weights=(nl == 1 or himpl == 3)))
-    t_gen = time.time() - t_gen
-    dl = dls[-1]                              # `layer` is its host copy (cpu_baseline / parity sample)
-    torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        rn.run_step(dls)
-    torch.cuda.synchronize()
-
-    ev = HipEvents(args.steps * nl)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        rn.plan()
-        for li in range(nl):
-            rn.run(dls[li], ev.pairs[i * nl + li][0], ev.pairs[i * nl + li][1])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps * nl)]
-    ev.close()
-    kern_avg_ms = float(np.mean(kern_ms))
-
-    total_tokens = batch.total_tokens
-    hidden_tokens = batch.hidden_tokens
-    kv_tokens = batch.kv_tokens
+    sweep = []
+    if do_sweep and nl == 1:
+        # the ratios other than the headline's first, so that the headline's buffers can stay for the oracle sample
+        for r in (0.0, 0.25, 0.5, 0.75, 1.0):
+            if abs(r - cfg.hidden_ratio) > 1e-9:
+                sweep.append(sweep_row(r, measure(wl.with_ratio(cfg, r), args, args.steps, args.warmup)))
+    head = measure(cfg, args, args.steps, args.warmup, keep=True)
+    rn, batch, layer, dls = head.pop("_keep")
+    if do_sweep and nl == 1:
+        sweep.append(sweep_row(cfg.hidden_ratio, head))
+        sweep.sort(key=lambda p: p["hidden_ratio"])
+    total_tokens, hidden_tokens, kv_tokens = batch.total_tokens, batch.hidden_tokens, batch.kv_tokens
     d, e = cfg.d_model, wl.ELEM_BYTES[cfg.dtype]
-    # cached tokens per second per decode layer: a step of nl layers serves total_tokens in each layer
-    value = total_tokens * nl / (ms_per_step * 1e-3)
+    himpl = HIMPL[args.hidden_impl]
 
-    # algorithmic work of the item kernel per launch
-    flops = 4.0 * d * d * hidden_tokens                 # K and V projections of hidden-kind tokens
-    kv_bytes = 2.0 * d * e * kv_tokens                  # K row + V row of KV-kind tokens
-    hid_bytes = 1.0 * d * e * hidden_tokens
-    t_mfma = flops / (PEAK_MFMA_TFLOPS[cfg.dtype] * 1e12)
-    t_hbm = (kv_bytes + hid_bytes) / (PEAK_HBM_GBS * 1e9)
-    wkey = f"{cfg.name}@{cfg.hidden_ratio:g}"
-    if rn.info.hidden_impl == 3 and hidden_tokens > 0:
-        # absorbed form: no projection; per hidden token and head one d_model-long dot product and one
-        # d_model-long weighted row update (4 d H flops, on the matrix cores with the fp32 operand split
-        # into 16-bit parts); the hidden rows are read twice.  Priced against HBM, on its own bytes.
-        flops = 4.0 * d * cfg.n_heads * hidden_tokens
-        hid_bytes = 2.0 * d * e * hidden_tokens
-        ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey + "@absorbed")}
-    elif t_mfma >= t_hbm:
-        ach = flops / (kern_avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
-                "frac": ach / PEAK_MFMA_TFLOPS[cfg.dtype], "traffic": read_traffic(wkey)}
-    else:
-        ach = (kv_bytes + hid_bytes) / (kern_avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": read_traffic(wkey)}
-    mfma_items = rn.info.n_hidden_items > 0 and rn.info.hidden_impl == 2
-    kname = "apt_items_mfma_kernel" if mfma_items else "apt_items_kernel"
-    if rn.info.hidden_impl == 3 and hidden_tokens > 0:
-        kname = "apt_absorb_{q,score,stats,pv,out,final}_kernel + apt_items_kernel (one event pair around all seven)"
-    roof.update({"kernel": kname, "kernel_ms": kern_avg_ms, "kernel_ms_min": float(np.min(kern_ms)),
-                 "algorithmic_flops": flops, "algorithmic_bytes": kv_bytes + hid_bytes})
-
+    roof = head["roofline"]
+    if roof["bound"] == "mfma":
+        roof["target_frac"] = 0.50
+        roof["note"] = ("MFMA fraction of the published dense peak on un-padded projection flops 4 d^2 per hidden token; "
+                        + ("below" if roof["frac"] < 0.5 else "at or above") + " the 0.50 target")
     result = {
         "metric": "cached tokens/sec per decode layer; HBM GB/s and MFMA util vs MI355X peak",
-        "value": value, "unit": "cached tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": "cached tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: d_model={d}, {cfg.n_heads} heads x {cfg.head_dim}, {cfg.dtype}, "
-                               f"batch {batch.B}, ctx {cfg.len_dist}[{cfg.len_lo},{cfg.len_hi}], block {cfg.block_size}, "
-                               f"{int(round(100 * cfg.hidden_ratio))}% hidden-cache requests"
-                               + (f", {nl} layers per step (one plan, {nl} attention calls)" if nl > 1 else ""),
-                   "layers_per_step": nl,
-                   "total_tokens": total_tokens, "hidden_tokens": hidden_tokens, "kv_tokens": kv_tokens,
-                   "hidden_impl": {1: "valu", 2: "mfma", 3: "absorbed"}[int(rn.info.hidden_impl)],
-                   "n_items": int(rn.info.n_items), "n_hidden_items": int(rn.info.n_hidden_items),
-                   "seed": cfg.seed, "input_gen_s": round(t_gen, 2)},
+        "config": dict({"workload": head["workload"]}, **head["config"]),
         "roofline": roof,
     }
 
@@ -218,7 +293,7 @@ def main():
         }
         result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
                                    "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
-    if nl == 1 and himpl == 0 and hidden_tokens > 0 and not args.no_next_rows and not args.sweep:
+    if nl == 1 and himpl == 0 and hidden_tokens > 0 and not args.no_next_rows:
         # context only: the same step with hidden-kind requests through the absorbed-weight form (no K/V
         # projection: not the paper's method, so it is never the headline and never priced in projection flops)
         rn2 = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=3)
@@ -237,12 +312,11 @@ def main():
         result["next_rows"] = {"absorbed_weight_hidden_path": {
             "ms_per_step": ms2, "cached_tokens_per_s": total_tokens / (ms2 * 1e-3),
             "max_abs_difference_to_default_path": dev,
-            "hbm_frac_on_own_bytes": (kv_bytes + 2.0 * d * e * hidden_tokens) / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS}}
+            "hbm_frac_on_own_bytes": (2.0 * d * e * kv_tokens + ABSORBED_X_READS * d * e * hidden_tokens) / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS}}
         del rn2, dl2
-    if args.sweep:
-        del rn, dls, dl
-        torch.cuda.empty_cache()
-        sweep = [time_ratio(cfg, r, args) for r in (0.0, 0.25, 0.5, 0.75, 1.0)]
+    del rn, dls, layer
+    torch.cuda.empty_cache()
+    if sweep:
         result["sweep"] = sweep
         # Section 4.2, Eq. 6 models the extra time of hidden-cache requests as t = rho * m, linear in
         # their cached length: least-squares line of the item-kernel time over the hidden tokens
@@ -250,49 +324,16 @@ def main():
         y = np.array([p["kernel_ms"] for p in sweep], dtype=np.float64)
         slope, icpt = np.polyfit(x, y, 1)
         resid = y - (slope * x + icpt)
-        result["rho_fit"] = {"rho_us_per_hidden_token": slope * 1e3, "intercept_ms": icpt,
-                             "r2": 1.0 - float((resid ** 2).sum() / ((y - y.mean()) ** 2).sum())}
+        result["rho_fit"] = {"workload": cfg.name, "rho_us_per_hidden_token": slope * 1e3, "intercept_ms": icpt,
+                             "r2": 1.0 - float((resid ** 2).sum() / ((y - y.mean()) ** 2).sum()),
+                             "points": len(sweep)}
+    if do_extras:
+        others = {}
+        for name, st, wu in (("opt13b", args.steps, args.warmup), ("opt30b", args.steps, args.warmup),
+                             ("opt13b_step", max(2, args.steps // 5), 1)):
+            others[name] = dict(brief(measure(wl.CONFIGS[name], args, st, wu)), steps=st, warmup=wu)
+        result["other_configs"] = others
     print(json.dumps(result))
-
-
-def time_ratio(cfg, ratio, args):
-    """Item-kernel time and roofline fractions of one hidden-cache ratio (same lengths, nested kind sets)."""
-    import numpy as np
-    import torch
-    from paper_2504_07494_amd import workloads as wl
-    from paper_2504_07494_amd.harness import DecodeRunner
-    c = wl.with_ratio(cfg, ratio)
-    batch = wl.make_batch(c)
-    layer = wl.make_layer(batch, workers=min(16, os.cpu_count() or 8))
-    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk,
-                      hidden_impl={"auto": 0, "valu": 1, "mfma": 2, "absorbed": 3}[args.hidden_impl])
-    dl = rn.upload(layer)
-    for _ in range(args.warmup):
-        rn.plan()
-        rn.run(dl)
-    torch.cuda.synchronize()
-    ev = HipEvents(args.steps)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        rn.plan()
-        rn.run(dl, ev.pairs[i][0], ev.pairs[i][1])
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    kms = float(np.mean([ev.elapsed_ms(i) for i in range(args.steps)]))
-    ev.close()
-    d, e = c.d_model, wl.ELEM_BYTES[c.dtype]
-    absorbed = int(rn.info.hidden_impl) == 3
-    flops = 4.0 * d * d * batch.hidden_tokens
-    nbytes = 2.0 * d * e * batch.kv_tokens + (2.0 if absorbed else 1.0) * d * e * batch.hidden_tokens
-    del rn, dl, layer
-    torch.cuda.empty_cache()
-    row = {"hidden_ratio": ratio, "total_tokens": batch.total_tokens, "hidden_tokens": batch.hidden_tokens,
-           "ms_per_step": ms_step, "kernel_ms": kms, "cached_tokens_per_s": batch.total_tokens / (ms_step * 1e-3),
-           "hbm_gbs": nbytes / (kms * 1e-3) / 1e9, "hbm_frac": nbytes / (kms * 1e-3) / 1e9 / PEAK_HBM_GBS}
-    if not absorbed:        # the absorbed form does no projection: it is never priced in projection flops
-        row.update({"mfma_tflops": flops / (kms * 1e-3) / 1e12,
-                    "mfma_frac": flops / (kms * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS[c.dtype]})
-    return row
 
 
 def run_sched_probe(args):

@@ -21,8 +21,11 @@
  *     (APT_OK) or a negative apt_status; apt_strerror() names it.
  *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
  *     memory of the current device.  The caller owns every buffer.  The library
- *     allocates no device memory and keeps no state between calls (apt_pool_* keep
- *     their state in the host handle the caller holds; apt_schedule is a pure function).
+ *     allocates no device memory.  The only state it keeps between calls is a small
+ *     per-device record made by apt_init() (compute-unit count, "kernel attributes are
+ *     set"), written once per device under a mutex and
+ *     read-only afterwards, so calls from several host threads are safe.  apt_pool_* keep
+ *     their state in the host handle the caller holds; apt_schedule is a pure function.
  *   - Launching functions take a HIP stream as void* (NULL = default stream) and
  *     return after enqueueing; inputs are read-only, only `out`, `workspace`,
  *     `packed` (apt_pack_weights), the cache pools (apt_cache_append, apt_cache_write) and one
@@ -109,14 +112,44 @@ typedef struct apt_plan_info {
     uint64_t workspace_bytes;   /* device workspace apt_hybrid_decode_attn needs          */
 } apt_plan_info;
 
+/* Utilities of the boundary (no counterpart in the paper): name of a status code; library
+ * version (major*10000 + minor*100 + patch). */
 const char* apt_strerror(int status);
-
-/* Library version (major*10000 + minor*100 + patch). */
 int apt_version(void);
 
 /*
+ * One-off set-up for the CURRENT device: reads the compute-unit count (the hidden-kind MFMA kernel
+ * runs one persistent workgroup per compute unit) and raises the dynamic-LDS limit of the kernels that
+ * need more than 64 KB.  Idempotent and thread-safe.  Every launching entry point calls it
+ * by itself on its first use on a device, so calling it is optional, EXCEPT before capturing calls
+ * into a HIP graph: call apt_init() (or run one eager call) on that device first, because setting
+ * kernel attributes is not a stream operation and does not belong into a capture.
+ * (Utility of the boundary; the operation it prepares is the attention step of Eq. 1-3.)
+ * Errors: APT_EHIP.
+ */
+int apt_init(void);
+
+/*
+ * Sizes a caller needs BEFORE any batch is known (Section 4.3: the cache pool and everything
+ * around it are set up once for the serving process; Section 4.2: batches of at most max_batch
+ * requests whose cache kinds change from iteration to iteration):
+ *   *dev_bytes   upper bound of apt_plan_info.workspace_bytes over every batch of 1..max_batch
+ *                requests with contexts of 1..max_ctx tokens and ANY mix of the two cache kinds.
+ *                For hidden_impl = APT_HIDDEN_AUTO, _VALU or _MFMA this is the partial-result
+ *                workspace (ranges of the shorter of the two chunk lengths); for
+ *                APT_HIDDEN_ABSORBED the sections of that path are added.  A workspace of this
+ *                size serves every such batch, so it can be allocated once.
+ *   *host_bytes  the same bound for the plan blob (= apt_plan_max_bytes), needed once on the host
+ *                and once on the device.
+ * Either pointer may be NULL.  Host only.  Errors: APT_EINVAL (max_batch < 1, max_ctx < 1, both
+ * pointers NULL), APT_ERANGE (max_ctx beyond max_blocks_per_req*block_size), APT_ESHAPE, APT_EDTYPE.
+ */
+int apt_workspace_bytes(const apt_shape* s, int max_batch, int max_ctx, size_t* dev_bytes, size_t* host_bytes);
+
+/*
  * Size in bytes of the largest plan blob a batch of B requests with contexts of at
- * most max_ctx tokens can need (host and device copy have the same size).
+ * most max_ctx tokens can need (host and device copy have the same size).  Helper of apt_plan
+ * (Section 4.2: one batch per iteration).
  */
 int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
 
@@ -154,18 +187,23 @@ int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t* bytes);
 int apt_plan(const apt_shape* s, const int32_t* ctx_lens_host, const uint8_t* cache_kind_host, int B,
              void* plan_host, size_t plan_bytes, apt_plan_info* info);
 
-/* Read the counts back from a plan blob made by apt_plan (host). */
+/* Read the counts back from a plan blob made by apt_plan (host; helper of apt_plan). */
 int apt_plan_get_info(const void* plan_host, apt_plan_info* info);
 
 /* Asynchronous copy of a plan blob to device memory (plan_dev: at least
- * info.plan_bytes bytes).  plan_host must stay unchanged until the copy is done;
- * use page-locked host memory for a truly asynchronous copy. */
+ * info.plan_bytes bytes; helper of apt_plan: the device half of the work partition).  plan_host
+ * must stay unchanged until the copy is done (re-planning into the same host buffer before that
+ * tears the copy: use one host buffer per step in flight, or wait for an event recorded after
+ * this call); use page-locked host memory for a truly asynchronous copy. */
 int apt_plan_upload(const void* plan_host, void* plan_dev, void* stream);
 
 /*
- * Debug helper (host): range-check a host copy of the cache maps.  Every entry of
+ * Debug helper (host): range-check a host copy of the cache maps (Section 4.3, "Cache Block
+ * Allocation": a cache map associates each token position of a request with a block of the
+ * unified pool; K and V lists for the KV kind, one list for the hidden kind).  Every entry of
  * the first ceil(n/block_size) positions of the rows a request uses must lie in
- * [0, n_pool_blocks).  Returns APT_ERANGE on the first violation.
+ * [0, n_pool_blocks).  Returns APT_ERANGE on the first violation, APT_EINVAL for a length < 1 or
+ * an unknown kind.
  */
 int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens_host, const uint8_t* cache_kind_host,
                       const int32_t* block_tables_host, int B, int64_t n_pool_blocks);
@@ -220,20 +258,6 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
  * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 128 (fp32 inputs: <= 40), and a larger workspace
  * (apt_plan_info.workspace_bytes says how much); hidden_chunk must be 0 or 512.
  */
-
-/*
- * The same step as apt_hybrid_decode_attn (Eq. 1-3 over both cache kinds); in addition
- * the HIP events ev_begin and ev_end (hipEvent_t handles created by the caller with
- * timing enabled; either may be NULL) are recorded on `stream` immediately before and
- * after the item kernel (with APT_HIDDEN_ABSORBED: before the first and after the last of the
- * kernels that run ahead of the merge), so that a caller can time it apart from the merge.
- */
-int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
-                                 const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
-                                 const void* W_K, const void* W_V, const void* W_packed,
-                                 const void* b_K, const void* b_V, const int32_t* block_tables,
-                                 void* out, void* workspace, size_t workspace_bytes, void* stream,
-                                 void* ev_begin, void* ev_end);
 
 /*
  * Hybrid cache assigner: host-side bookkeeping of the unified block pool (Section 4.3,
@@ -323,25 +347,6 @@ int apt_cache_write(const apt_shape* s, int B, const int32_t* new_offsets_dev, i
                     const void* x_new, const void* k_new, const void* v_new, void* k_pages, void* v_pages,
                     void* hidden_pages, const int32_t* block_tables, const int32_t* ctx_lens_dev,
                     const uint8_t* cache_kind_dev, void* stream);
-
-/*
- * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16; device
- * pointers, 16-byte aligned).  Exists so that hardware traffic counters can be
- * calibrated against a kernel of known traffic (reads `bytes`, writes `bytes`).
- */
-int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
-
-/*
- * Register-only fp16 MFMA loop (no memory traffic): n_workgroups workgroups of 256
- * threads, each wave issuing iters * 16 independent 32x32x16 MFMAs
- * (n_workgroups * 4 * iters * 16 * 32768 flops in total).  random_operands = 0: constant
- * operands; != 0: operands of magnitude ~1 with random mantissas and signs, which is what
- * the multipliers see with real data (the sustained clock under the board's power limit
- * depends on it).  `out` (device) receives n_workgroups * 256 floats.  Exists to measure the
- * rate the matrix pipes sustain on the device at hand, as context for the MFMA roofline
- * fraction.
- */
-int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, void* stream);
 
 #ifdef __cplusplus
 }

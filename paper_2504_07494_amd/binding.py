@@ -20,11 +20,13 @@ APT_HIDDEN_AUTO, APT_HIDDEN_VALU, APT_HIDDEN_MFMA, APT_HIDDEN_ABSORBED = 0, 1, 2
 APT_OK, APT_EINVAL, APT_ESHAPE, APT_EDTYPE, APT_EWORKSPACE, APT_EHIP, APT_ERANGE, APT_EFULL = 0, -1, -2, -3, -4, -5, -6, -7
 DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 
-EXPORTS = ["apt_strerror", "apt_version", "apt_plan_max_bytes", "apt_plan", "apt_plan_get_info", "apt_plan_upload",
-           "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights", "apt_hybrid_decode_attn",
-           "apt_hybrid_decode_attn_timed", "apt_cache_append", "apt_cache_write", "apt_copy_bytes", "apt_probe_mfma",
+# include/apt_hybrid.h (the product interface) and include/apt_hybrid_bench.h (measurement tooling)
+EXPORTS = ["apt_strerror", "apt_version", "apt_init", "apt_workspace_bytes", "apt_plan_max_bytes", "apt_plan",
+           "apt_plan_get_info", "apt_plan_upload", "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights",
+           "apt_hybrid_decode_attn", "apt_cache_append", "apt_cache_write",
            "apt_pool_create", "apt_pool_destroy", "apt_pool_free_blocks", "apt_pool_blocks_needed", "apt_pool_assign",
            "apt_pool_extend", "apt_pool_release", "apt_pool_switch_kind", "apt_pool_export", "apt_schedule"]
+BENCH_EXPORTS = ["apt_hybrid_decode_attn_timed", "apt_copy_bytes", "apt_probe_mfma"]
 
 
 class apt_shape(C.Structure):
@@ -59,7 +61,7 @@ def lib():
         _lib = C.CDLL(LIB_PATH)
         _lib.apt_strerror.restype = C.c_char_p
         _lib.apt_strerror.argtypes = [C.c_int]
-        for name in EXPORTS[1:]:
+        for name in EXPORTS[1:] + BENCH_EXPORTS:
             getattr(_lib, name).restype = C.c_int
         _lib.apt_pool_destroy.restype = None
     return _lib
@@ -97,6 +99,18 @@ def make_shape(d_model, n_heads, head_dim, block_size, dtype, max_blocks_per_req
                out_dtype="f32", hidden_chunk=0, kv_chunk=0, hidden_impl=APT_HIDDEN_AUTO) -> apt_shape:
     return apt_shape(d_model, n_heads, head_dim, block_size, DTYPE_CODES[dtype], DTYPE_CODES[out_dtype],
                      max_blocks_per_req, hidden_chunk, kv_chunk, hidden_impl, float(softmax_scale), 0)
+
+
+def apt_init():
+    _check(lib().apt_init(), "apt_init")
+
+
+def apt_workspace_bytes(shape, max_batch, max_ctx):
+    """Returns (dev_bytes, host_bytes)."""
+    dev, host = C.c_size_t(), C.c_size_t()
+    _check(lib().apt_workspace_bytes(C.byref(shape), C.c_int(max_batch), C.c_int(max_ctx), C.byref(dev), C.byref(host)),
+           "apt_workspace_bytes")
+    return dev.value, host.value
 
 
 def apt_plan_max_bytes(shape, B, max_ctx) -> int:

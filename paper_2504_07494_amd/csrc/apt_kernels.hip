@@ -15,7 +15,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <mutex>
 #include "apt_internal.h"
+#include "apt_hybrid_bench.h"
 
 namespace {
 
@@ -864,6 +866,7 @@ __global__ __launch_bounds__(kThreads) void apt_write_kernel(const int32_t* new_
     const int r = blockIdx.x;
     const int row0 = new_offsets[r], n_new = new_offsets[r + 1] - row0;
     const int first = ctx_lens[r] - n_new;              // position of the first new token
+    if (n_new <= 0 || first < 0) return;                // more new tokens than the request holds: nothing is written
     const int64_t blk_bytes = (int64_t)bs * d * eb;
     const int row_units = d * eb / 16, head_units = hd * eb / 16;
     const bool hidden = cache_kind[r] == APT_KIND_HIDDEN;
@@ -936,12 +939,6 @@ __global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, in
 template <int DT, int HD, int HIMPL>
 int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
     auto kern = apt_items_kernel<DT, HD, HIMPL>;
-    static bool attr_done = false;
-    if (lds_bytes > 64 * 1024 && !attr_done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return APT_EHIP;
-        attr_done = true;
-    }
     hipLaunchKernelGGL(kern, dim3(p.n_items - p.item_base), dim3(kThreads), lds_bytes, st, p);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
@@ -950,23 +947,13 @@ int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
 
 // persistent launch: one workgroup per compute unit, a multiple of 8
 template <int DT>
-int launch_mfma(const ItemParams& p, hipStream_t st) {
-    auto kern = apt_items_mfma_kernel<DT>;
-    static int n_wg = 0;
-    if (n_wg == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return APT_EHIP;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return APT_EHIP;
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return APT_EHIP;
-        n_wg = cus >= 8 ? (cus / 8) * 8 : 8;
-    }
-    hipLaunchKernelGGL(kern, dim3(n_wg), dim3(kThreads), kMfmaLds, st, p);
+int launch_mfma(const ItemParams& p, int n_wg, hipStream_t st) {
+    hipLaunchKernelGGL(apt_items_mfma_kernel<DT>, dim3(n_wg), dim3(kThreads), kMfmaLds, st, p);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
 template <int DT, int HD>
-int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtype, hipStream_t st) {
+int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtype, int n_wg, hipStream_t st) {
     constexpr int EB = Elt<DT>::bytes;
     constexpr int LPR = HD * EB / 16;
     constexpr int G = 4 * (64 / LPR);
@@ -984,12 +971,55 @@ int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtyp
         return launch_items<DT, HD, 1>(p, v > kv_lds ? v : kv_lds, st);
     }
     if constexpr (DT != 0 && HD == 128) {
-        return launch_mfma<DT>(p, st);
+        return launch_mfma<DT>(p, n_wg, st);
     }
     return APT_ESHAPE;
 }
 
+// ---------------------------------------------------------------------------------
+// per-device set-up: made once per device under a mutex, read-only afterwards
+// ---------------------------------------------------------------------------------
+struct DeviceState {
+    bool ready = false;
+    int n_wg = 0;             // workgroups of the persistent MFMA launch
+};
+constexpr int kMaxDevices = 64;
+std::mutex g_setup_mutex;
+DeviceState g_devices[kMaxDevices];
+
+template <typename K> bool raise_lds_limit(K kern) {
+    return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
+}
+
+int device_setup(const DeviceState** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return APT_EHIP;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    DeviceState& ds = g_devices[dev];
+    if (!ds.ready) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return APT_EHIP;
+        ds.n_wg = cus >= 8 ? (cus / 8) * 8 : 8;
+        // every kernel that can be launched with more than 64 KB of dynamic LDS
+        const bool ok = raise_lds_limit(apt_items_mfma_kernel<1>) && raise_lds_limit(apt_items_mfma_kernel<2>) &&
+                        raise_lds_limit(apt_items_kernel<0, 64, 1>) && raise_lds_limit(apt_items_kernel<0, 128, 1>) &&
+                        raise_lds_limit(apt_items_kernel<1, 64, 1>) && raise_lds_limit(apt_items_kernel<1, 128, 1>) &&
+                        raise_lds_limit(apt_items_kernel<2, 64, 1>) && raise_lds_limit(apt_items_kernel<2, 128, 1>) &&
+                        raise_lds_limit(apt_absorb_score_kernel<0>) && raise_lds_limit(apt_absorb_pv_kernel<0>) &&
+                        raise_lds_limit(apt_absorb_score_mfma_kernel<1>) && raise_lds_limit(apt_absorb_score_mfma_kernel<2>) &&
+                        raise_lds_limit(apt_absorb_pv_mfma_kernel<1>) && raise_lds_limit(apt_absorb_pv_mfma_kernel<2>);
+        if (!ok) return APT_EHIP;
+        ds.ready = true;
+    }
+    if (out) *out = &ds;
+    return APT_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
 }  // namespace
+
+extern "C" int apt_init(void) { return device_setup(nullptr); }
 
 extern "C" int apt_plan_upload(const void* plan_host, void* plan_dev, void* stream) {
     apt_plan_info info;
@@ -1033,6 +1063,9 @@ extern "C" int apt_cache_append(const apt_shape* s, int B, const void* x_new, co
     if (B < 1 || !block_tables || !ctx_lens_dev || !cache_kind_dev) return APT_EINVAL;
     if (!x_new && !k_new && !v_new) return APT_EINVAL;
     if ((x_new && !hidden_pages) || ((k_new || v_new) && (!k_new || !v_new || !k_pages || !v_pages))) return APT_EINVAL;
+    if (!aligned16(x_new) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pages) || !aligned16(v_pages) ||
+        !aligned16(hidden_pages))
+        return APT_EINVAL;
     int log2_bs = 0;
     while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
     hipLaunchKernelGGL(apt_append_kernel, dim3(B), dim3(kThreads), 0, (hipStream_t)stream, (const char*)x_new,
@@ -1052,6 +1085,9 @@ extern "C" int apt_cache_write(const apt_shape* s, int B, const int32_t* new_off
     if (B < 1 || max_new_tokens < 1 || !new_offsets_dev || !block_tables || !ctx_lens_dev || !cache_kind_dev) return APT_EINVAL;
     if (!x_new && !k_new && !v_new) return APT_EINVAL;
     if ((x_new && !hidden_pages) || ((k_new || v_new) && (!k_new || !v_new || !k_pages || !v_pages))) return APT_EINVAL;
+    if (!aligned16(x_new) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pages) || !aligned16(v_pages) ||
+        !aligned16(hidden_pages))
+        return APT_EINVAL;
     int log2_bs = 0;
     while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
     const unsigned groups = (unsigned)((max_new_tokens + kWriteTokens - 1) / kWriteTokens);
@@ -1104,7 +1140,13 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     const apt_ws_layout L = apt_ws_sections(pw[APT_PW_NPARTIALS], rs.s.n_heads, rs.s.head_dim, rs.s.hidden_impl,
                                             pw[APT_PW_NHIDREQ], hidden_tokens, n_hidden, rs.s.d_model, rs.s.dtype);
     if (workspace_bytes < L.total) return APT_EWORKSPACE;
-    if (((uintptr_t)workspace & 15) != 0) return APT_EINVAL;
+    // 16-byte vector loads and stores: every base pointer has to be 16-byte aligned
+    if (!aligned16(workspace) || !aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(hidden_pages) ||
+        !aligned16(W_K) || !aligned16(W_V) || !aligned16(W_packed) || !aligned16(b_K) || !aligned16(b_V) || !aligned16(plan_dev))
+        return APT_EINVAL;
+    const DeviceState* ds = nullptr;
+    rc = device_setup(&ds);
+    if (rc) return rc;
     if (n_hidden < n_items && (!k_pages || !v_pages)) return APT_EINVAL;
     if (n_hidden > 0) {
         if (!hidden_pages || !b_K || !b_V) return APT_EINVAL;
@@ -1149,12 +1191,12 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
 
     const int dt = rs.s.dtype, hd = rs.s.head_dim, hi = rs.s.hidden_impl;
     if (ev_begin && hipEventRecord((hipEvent_t)ev_begin, st) != hipSuccess) return APT_EHIP;
-    if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
-    else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
-    else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
-    else if (dt == APT_F16 && hd == 128) rc = launch_items_impl<1, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
-    else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, (char*)out, rs.s.out_dtype, st);
-    else rc = launch_items_impl<2, 128>(p, hi, (char*)out, rs.s.out_dtype, st);
+    if (dt == APT_F32 && hd == 64) rc = launch_items_impl<0, 64>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
+    else if (dt == APT_F32 && hd == 128) rc = launch_items_impl<0, 128>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
+    else if (dt == APT_F16 && hd == 64) rc = launch_items_impl<1, 64>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
+    else if (dt == APT_F16 && hd == 128) rc = launch_items_impl<1, 128>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
+    else if (dt == APT_BF16 && hd == 64) rc = launch_items_impl<2, 64>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
+    else rc = launch_items_impl<2, 128>(p, hi, (char*)out, rs.s.out_dtype, ds->n_wg, st);
     if (rc) return rc;
     if (ev_end && hipEventRecord((hipEvent_t)ev_end, st) != hipSuccess) return APT_EHIP;
 

@@ -86,6 +86,26 @@ extern "C" int apt_plan_max_bytes(const apt_shape* s, int B, int max_ctx, size_t
     return APT_OK;
 }
 
+extern "C" int apt_workspace_bytes(const apt_shape* s, int max_batch, int max_ctx, size_t* dev_bytes, size_t* host_bytes) {
+    apt_resolved rs;
+    int rc = apt_resolve(s, &rs);
+    if (rc) return rc;
+    if (max_batch < 1 || max_ctx < 1 || (!dev_bytes && !host_bytes)) return APT_EINVAL;
+    if ((int64_t)max_ctx > (int64_t)rs.s.max_blocks_per_req * rs.s.block_size) return APT_ERANGE;
+    // every workspace section grows with each of these counts, so the layout of their separate maxima bounds
+    // the layout of any batch: ranges are most numerous when every request is of the kind with the shorter
+    // chunk; the sections of the absorbed-weight path are largest when every request is hidden-kind
+    const int cmin = rs.s.hidden_chunk < rs.s.kv_chunk ? rs.s.hidden_chunk : rs.s.kv_chunk;
+    const int64_t n_partials = (int64_t)max_batch * ceil_div64(max_ctx, cmin);
+    const int64_t hid_chunks = (int64_t)max_batch * ceil_div64(max_ctx, rs.s.hidden_chunk);
+    if (n_partials * (int64_t)rs.s.n_heads > 0x7fffffff || (int64_t)max_batch * max_ctx > 0x7fffffff) return APT_ERANGE;
+    if (dev_bytes)
+        *dev_bytes = (size_t)apt_ws_sections(n_partials, rs.s.n_heads, rs.s.head_dim, rs.s.hidden_impl, max_batch,
+                                             (int64_t)max_batch * max_ctx, hid_chunks, rs.s.d_model, rs.s.dtype).total;
+    if (host_bytes) return apt_plan_max_bytes(s, max_batch, max_ctx, host_bytes);
+    return APT_OK;
+}
+
 extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8_t* cache_kind, int B,
                         void* plan_host, size_t plan_bytes, apt_plan_info* info) {
     apt_resolved rs;

@@ -61,25 +61,41 @@ class DecodeRunner:
                                    out_dtype=out_dtype, hidden_chunk=hidden_chunk, kv_chunk=kv_chunk,
                                    hidden_impl=hidden_impl)
         max_ctx = batch.max_blocks * cfg.block_size
-        nbytes = ab.apt_plan_max_bytes(self.shape, batch.B, max_ctx)
-        self.plan_host = torch.empty(nbytes // 4, dtype=torch.int32, pin_memory=True)
-        self.plan_dev = torch.empty(nbytes // 4, dtype=torch.int32, device=self.device)
+        # sized once for every batch of at most B requests of this shape, whatever their lengths and kinds
+        ws_bytes, plan_bytes = ab.apt_workspace_bytes(self.shape, batch.B, max_ctx)
+        # The plan blob is written on the host and copied asynchronously: a host buffer is rewritten only after the
+        # copy that last read it has completed (one event per buffer), so steps can be planned back to back
+        # without a device synchronisation and without tearing a pending copy.
+        self._plan_bufs = [torch.empty(plan_bytes // 4, dtype=torch.int32, pin_memory=True) for _ in range(2)]
+        self._plan_events = [None] * len(self._plan_bufs)
+        self._plan_i = 0
+        self.plan_host = self._plan_bufs[0]
+        self.plan_dev = torch.empty(plan_bytes // 4, dtype=torch.int32, device=self.device)
         self.block_tables = torch.from_numpy(batch.block_tables).to(self.device)
         self.out = torch.empty((batch.B, cfg.n_heads, cfg.head_dim), dtype=_TORCH_OUT[out_dtype], device=self.device)
+        self.workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=self.device)
         self.info = None
-        self.workspace = None
+        ab.apt_init()
         self.plan()
 
     def stream(self) -> int:
         return torch.cuda.current_stream(self.device).cuda_stream
 
-    def plan(self):
-        """a1: partition on the host, copy the blob to the device."""
-        self.info = ab.apt_plan(self.shape, self.batch.ctx_lens, self.batch.cache_kind, self.plan_host)
+    def plan(self, ctx_lens=None, cache_kind=None):
+        """a1: partition on the host, copy the blob to the device.  ctx_lens / cache_kind: this step's lengths and
+        kinds (default: the batch's own); lengths must stay within what the cache maps cover."""
+        ctx_lens = self.batch.ctx_lens if ctx_lens is None else np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        cache_kind = self.batch.cache_kind if cache_kind is None else np.ascontiguousarray(cache_kind, dtype=np.uint8)
+        i = self._plan_i = (self._plan_i + 1) % len(self._plan_bufs)
+        if self._plan_events[i] is not None:
+            self._plan_events[i].synchronize()        # the copy out of this host buffer is done
+        self.plan_host = self._plan_bufs[i]
+        self.info = ab.apt_plan(self.shape, ctx_lens, cache_kind, self.plan_host)
         ab.apt_plan_upload(self.plan_host, self.plan_dev, self.stream())
-        need = int(self.info.workspace_bytes)
-        if self.workspace is None or self.workspace.numel() < need:
-            self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=self.device)
+        ev = torch.cuda.Event()
+        ev.record(torch.cuda.current_stream(self.device))
+        self._plan_events[i] = ev
+        assert int(self.info.workspace_bytes) <= self.workspace.numel()
         return self.info
 
     def upload(self, layer: wl.Layer, separate_pools: bool = False, keep_raw_weights: bool = True) -> DeviceLayer:

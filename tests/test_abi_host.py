@@ -20,16 +20,52 @@ def _shape(**kw):
     return ab.make_shape(**base)
 
 
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)          # declarations only, not the prose about them
+    return set(re.findall(r"\b(apt_[a-z_0-9]+)\s*\(", header))
+
+
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "apt_hybrid.h")).read()
-    declared = set(re.findall(r"\b(apt_[a-z_0-9]+)\s*\(", header))
-    declared -= {"apt_status"}
+    declared = _declared("apt_hybrid.h")
     assert declared == set(ab.EXPORTS), declared ^ set(ab.EXPORTS)
+    bench = _declared("apt_hybrid_bench.h")
+    assert bench == set(ab.BENCH_EXPORTS), bench ^ set(ab.BENCH_EXPORTS)
     lib = ab.lib()
-    for name in declared:
+    for name in declared | bench:
         assert hasattr(lib, name), name
     assert ab.apt_version() >= 100
     assert ab.apt_strerror(0) == "ok" and "shape" in ab.apt_strerror(ab.APT_ESHAPE)
+
+
+@pytest.mark.parametrize("himpl", [ab.APT_HIDDEN_AUTO, ab.APT_HIDDEN_VALU, ab.APT_HIDDEN_MFMA, ab.APT_HIDDEN_ABSORBED])
+def test_workspace_bound_covers_every_batch(himpl):
+    """apt_workspace_bytes(max_batch, max_ctx) is at least what any batch within those limits needs, for every
+    mix of the two cache kinds, and the all-one-kind extremes show that it is not a loose guess."""
+    g = np.random.default_rng(11 + himpl)
+    for kw in (dict(), dict(d_model=9216, n_heads=72), dict(d_model=256, n_heads=4, head_dim=64, dtype="f32")):
+        if himpl == ab.APT_HIDDEN_MFMA and kw.get("dtype") == "f32":
+            continue
+        shape = _shape(hidden_impl=himpl, **kw)
+        max_batch, max_ctx = 48, 2048
+        dev, host = ab.apt_workspace_bytes(shape, max_batch, max_ctx)
+        assert host == ab.apt_plan_max_bytes(shape, max_batch, max_ctx)
+        worst = 0
+        for trial in range(30):
+            B = int(g.integers(1, max_batch + 1)) if trial else max_batch
+            lens = g.integers(1, max_ctx + 1, size=B) if trial > 2 else np.full(B, max_ctx)
+            ratio = [1.0, 0.0, 0.5][trial] if trial < 3 else g.random()
+            kinds = (g.random(B) < ratio).astype(np.uint8)
+            buf, info = _plan(shape, lens, kinds)
+            assert info.workspace_bytes <= dev and info.plan_bytes <= host
+            worst = max(worst, int(info.workspace_bytes))
+        assert worst >= 0.5 * dev
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_workspace_bytes(_shape(), 0, 100)
+    assert e.value.status == ab.APT_EINVAL
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_workspace_bytes(_shape(), 4, 128 * 16 + 1)
+    assert e.value.status == ab.APT_ERANGE
 
 
 def _plan(shape, lens, kinds):

@@ -11,9 +11,10 @@ from tests.helpers import oracle_attn
 pytestmark = pytest.mark.gpu
 
 
-def _sample_pairs(batch, n_random, seed):
+def _sample_pairs(batch, n_random, seed, every_request=True):
     """Shortest and longest request, lengths = 0, 1, 15 mod 16 when present, both kinds,
-    plus random pairs."""
+    plus random pairs, plus (every_request) one head of EVERY request, drawn so that the
+    requests spread evenly over the eight head queues (head % 8) of the hidden-kind items."""
     cfg = batch.cfg
     g = np.random.default_rng(seed)
     lens, kinds = batch.ctx_lens, batch.cache_kind
@@ -30,10 +31,14 @@ def _sample_pairs(batch, n_random, seed):
     pairs = [(int(r), int(g.integers(cfg.n_heads))) for r in picks]
     flat = g.choice(batch.B * cfg.n_heads, size=n_random, replace=False)
     pairs += [(int(f // cfg.n_heads), int(f % cfg.n_heads)) for f in flat]
+    if every_request:
+        for r in range(batch.B):
+            queue = [h for h in range(cfg.n_heads) if h % 8 == r % 8]
+            pairs.append((r, int(g.choice(queue))))
     return sorted(set(pairs))
 
 
-def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_impl=0):
+def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_impl=0, every_request=True):
     from paper_2504_07494_amd.harness import DecodeRunner
     print(f"[case] full size {cfg.name} ratio={cfg.hidden_ratio} hidden_impl={hidden_impl}", flush=True)
     batch = wl.make_batch(cfg)
@@ -43,7 +48,8 @@ def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_imp
     rn.run(dl)
     got = rn.out_f64()
     assert np.all(np.isfinite(got))
-    pairs = _sample_pairs(batch, n_random, cfg.seed)
+    pairs = _sample_pairs(batch, n_random, cfg.seed, every_request)
+    assert not every_request or {p[0] for p in pairs} == set(range(batch.B))
     want = oracle_attn(oracle, batch, layer, pairs=pairs)
     sel = got[[p[0] for p in pairs], [p[1] for p in pairs]]
     err = np.abs(sel - want)
@@ -111,8 +117,10 @@ def test_opt13b_bf16_all_hidden_absorbed_weight_path(oracle):
     _run_and_check(oracle, cfg, n_random=12, hidden_impl=ab.APT_HIDDEN_ABSORBED)
 
 
-@pytest.mark.parametrize("ratio", [0.0, 0.5, 1.0])
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("ratio", [0.0, 0.25, 0.5, 0.75, 1.0])
 def test_opt66b_layer_ratio_sweep(oracle, ratio):
+    """Every point of the hidden-cache ratio sweep bench.py times; every request is compared on at least one head."""
     _run_and_check(oracle, wl.with_ratio(wl.CONFIGS["opt66b"], ratio), n_random=10)
 
 
@@ -146,7 +154,7 @@ def test_full_decode_step_forty_layers_bf16(oracle):
     rn.run_step(layers, outs)
     torch.cuda.synchronize()
     first = [o.clone() for o in outs]
-    pairs = _sample_pairs(batch, 12, cfg.seed)
+    pairs = _sample_pairs(batch, 12, cfg.seed)      # every request on one head, in each of the three layers
     for li in sorted(checked):
         got = outs[li].float().cpu().numpy().astype(np.float64)
         assert np.all(np.isfinite(got))

@@ -267,3 +267,36 @@ def test_device_plan_copy_matches_host_plan(oracle):
     torch.cuda.synchronize()
     n = int(rn.info.plan_bytes) // 4
     assert np.array_equal(rn.plan_dev[:n].cpu().numpy(), rn.plan_host[:n].numpy())
+
+
+def test_steps_with_changing_lengths_back_to_back_without_a_device_sync(oracle):
+    """A decode loop re-plans every step while earlier steps are still queued: each step's plan copy must reach
+    the device intact (the host blob of a pending copy is never rewritten).  Five steps with different lengths
+    and kinds are enqueued without any synchronisation; every step's output is then compared with the oracle."""
+    print("[case] back-to-back re-planning", flush=True)
+    from paper_2504_07494_amd.harness import DecodeRunner
+    cfg = wl.small_config(name="replan", dtype="f16", d_model=1024, n_heads=8, head_dim=128, block_size=16, batch=24,
+                          len_lo=600, len_hi=1500, hidden_ratio=0.5)
+    batch = wl.make_batch(cfg)
+    layer = wl.make_layer(batch)
+    rn = DecodeRunner(batch)
+    dl = rn.upload(layer)
+    g = np.random.default_rng(7)
+    steps = []
+    for i in range(5):
+        lens = np.maximum(1, (batch.ctx_lens * g.uniform(0.05, 1.0, size=batch.B)).astype(np.int32))
+        if i == 4:
+            lens = batch.ctx_lens.copy()
+        steps.append((lens, batch.cache_kind.copy()))
+    outs = [torch.empty_like(rn.out) for _ in steps]
+    torch.cuda.synchronize()
+    for (lens, kinds), out in zip(steps, outs):      # no synchronisation inside this loop
+        rn.plan(lens, kinds)
+        rn.run(dl, out=out)
+    torch.cuda.synchronize()
+    c = batch.cfg
+    for i, ((lens, kinds), out) in enumerate(zip(steps, outs)):
+        want = oracle.attn(oracle.shape_of(c.d_model, c.n_heads, c.head_dim, c.block_size, c.dtype, batch.max_blocks,
+                                           c.softmax_scale), layer.q, layer.pool, layer.pool, layer.pool, layer.W_K,
+                           layer.b_K, layer.W_V, layer.b_V, batch.block_tables, lens, kinds).reshape(out.shape)
+        _check(out.float().cpu().numpy().astype(np.float64), want, f"replan step {i}")

@@ -23,7 +23,7 @@
  *     memory of the current device.  The caller owns every buffer.  The library
  *     allocates no device memory.  The only state it keeps between calls is a small
  *     per-device record made by apt_init() (compute-unit count, "kernel attributes are
- *     set"), written once per device under a mutex and
+ *     set", address of the static workspace), written once per device under a mutex and
  *     read-only afterwards, so calls from several host threads are safe.  apt_pool_* keep
  *     their state in the host handle the caller holds; apt_schedule is a pure function.
  *   - Launching functions take a HIP stream as void* (NULL = default stream) and
@@ -119,8 +119,9 @@ int apt_version(void);
 
 /*
  * One-off set-up for the CURRENT device: reads the compute-unit count (the hidden-kind MFMA kernel
- * runs one persistent workgroup per compute unit) and raises the dynamic-LDS limit of the kernels that
- * need more than 64 KB.  Idempotent and thread-safe.  Every launching entry point calls it
+ * runs one persistent workgroup per compute unit), raises the dynamic-LDS limit of the kernels that
+ * need more than 64 KB, and looks up the device address of the static workspace used by
+ * apt_hybrid_decode_attn_static.  Idempotent and thread-safe.  Every launching entry point calls it
  * by itself on its first use on a device, so calling it is optional, EXCEPT before capturing calls
  * into a HIP graph: call apt_init() (or run one eager call) on that device first, because setting
  * kernel attributes is not a stream operation and does not belong into a capture.
@@ -258,6 +259,27 @@ int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan
  * the raw W_K, W_V (not W_packed), d_model a multiple of 32, n_heads <= 128 (fp32 inputs: <= 40), and a larger workspace
  * (apt_plan_info.workspace_bytes says how much); hidden_chunk must be 0 or 512.
  */
+
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same step as apt_hybrid_decode_attn with the
+ * partial-result workspace taken from a static device array inside the library instead of a
+ * caller buffer.  Arguments as for apt_hybrid_decode_attn, without workspace / workspace_bytes.
+ * The array has APT_STATIC_WORKSPACE_BYTES bytes per device (each GPU the library runs on holds it
+ * until the process ends); a plan that needs more (apt_plan_info.workspace_bytes) is rejected with
+ * APT_EWORKSPACE, and so is APT_HIDDEN_ABSORBED (its workspace is far larger: APT_ESHAPE).  The call
+ * allocates nothing and frees nothing.  Every partial the merge reads is written earlier in the same
+ * call, so nothing needs clearing between calls; the array keeps the last call's partials.  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two host
+ * threads) race and give wrong results; order them on one stream.  Call apt_init() before
+ * capturing this call into a graph.
+ */
+#define APT_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int apt_hybrid_decode_attn_static(const apt_shape* s, const void* plan_host, void* plan_dev,
+                                  const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                  const void* W_K, const void* W_V, const void* W_packed,
+                                  const void* b_K, const void* b_V, const int32_t* block_tables,
+                                  void* out, void* stream);
 
 /*
  * Hybrid cache assigner: host-side bookkeeping of the unified block pool (Section 4.3,

@@ -23,7 +23,7 @@ DTYPE_CODES = {"f32": APT_F32, "f16": APT_F16, "bf16": APT_BF16}
 # include/apt_hybrid.h (the product interface) and include/apt_hybrid_bench.h (measurement tooling)
 EXPORTS = ["apt_strerror", "apt_version", "apt_init", "apt_workspace_bytes", "apt_plan_max_bytes", "apt_plan",
            "apt_plan_get_info", "apt_plan_upload", "apt_validate_host", "apt_packed_weight_bytes", "apt_pack_weights",
-           "apt_hybrid_decode_attn", "apt_cache_append", "apt_cache_write",
+           "apt_hybrid_decode_attn", "apt_hybrid_decode_attn_static", "apt_cache_append", "apt_cache_write",
            "apt_pool_create", "apt_pool_destroy", "apt_pool_free_blocks", "apt_pool_blocks_needed", "apt_pool_assign",
            "apt_pool_extend", "apt_pool_release", "apt_pool_switch_kind", "apt_pool_export", "apt_schedule"]
 BENCH_EXPORTS = ["apt_hybrid_decode_attn_timed", "apt_copy_bytes", "apt_probe_mfma"]
@@ -162,6 +162,17 @@ def apt_hybrid_decode_attn(shape, plan_host, plan_dev, q, k_pages, v_pages, hidd
                                         _ptr(v_pages), _ptr(hidden_pages), _ptr(W_K), _ptr(W_V), _ptr(W_packed),
                                         _ptr(b_K), _ptr(b_V), _ptr(block_tables), _ptr(out), _ptr(workspace),
                                         C.c_size_t(workspace_bytes), C.c_void_p(stream)), "apt_hybrid_decode_attn")
+
+
+APT_STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def apt_hybrid_decode_attn_static(shape, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed,
+                                  b_K, b_V, block_tables, out, stream=0):
+    _check(lib().apt_hybrid_decode_attn_static(C.byref(shape), _ptr(plan_host), _ptr(plan_dev), _ptr(q), _ptr(k_pages),
+                                               _ptr(v_pages), _ptr(hidden_pages), _ptr(W_K), _ptr(W_V), _ptr(W_packed),
+                                               _ptr(b_K), _ptr(b_V), _ptr(block_tables), _ptr(out), C.c_void_p(stream)),
+           "apt_hybrid_decode_attn_static")
 
 
 def apt_hybrid_decode_attn_timed(shape, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed,

@@ -19,6 +19,10 @@
 #include "apt_internal.h"
 #include "apt_hybrid_bench.h"
 
+// Workspace of apt_hybrid_decode_attn_static: one copy per device, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; the device address is looked up once per device (device_setup).
+static __device__ __align__(256) unsigned char scratch[APT_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 constexpr float kSentinel = -1.0e30f;   // "no score yet": finite, so differences never give NaN
@@ -982,6 +986,7 @@ int launch_items_impl(const ItemParams& p_in, int himpl, char* out, int out_dtyp
 struct DeviceState {
     bool ready = false;
     int n_wg = 0;             // workgroups of the persistent MFMA launch
+    void* scratch_ptr = nullptr;  // this device's copy of the static workspace
 };
 constexpr int kMaxDevices = 64;
 std::mutex g_setup_mutex;
@@ -1009,6 +1014,9 @@ int device_setup(const DeviceState** out) {
                         raise_lds_limit(apt_absorb_score_mfma_kernel<1>) && raise_lds_limit(apt_absorb_score_mfma_kernel<2>) &&
                         raise_lds_limit(apt_absorb_pv_mfma_kernel<1>) && raise_lds_limit(apt_absorb_pv_mfma_kernel<2>);
         if (!ok) return APT_EHIP;
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return APT_EHIP;
+        ds.scratch_ptr = ptr;
         ds.ready = true;
     }
     if (out) *out = &ds;
@@ -1116,16 +1124,20 @@ extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, int random
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
-                                            const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
-                                            const void* W_K, const void* W_V, const void* W_packed,
-                                            const void* b_K, const void* b_V, const int32_t* block_tables,
-                                            void* out, void* workspace, size_t workspace_bytes, void* stream,
-                                            void* ev_begin, void* ev_end) {
+// The attention step behind all three entry points.  static_ws: the partials go to this device's static workspace
+// (workspace / workspace_bytes are ignored) and nothing may be allocated.
+static int decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev,
+                       const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                       const void* W_K, const void* W_V, const void* W_packed,
+                       const void* b_K, const void* b_V, const int32_t* block_tables,
+                       void* out, void* workspace, size_t workspace_bytes, bool static_ws, void* stream,
+                       void* ev_begin, void* ev_end) {
     apt_resolved rs;
     int rc = apt_resolve(s, &rs);
     if (rc) return rc;
-    if (!plan_host || !plan_dev || !q || !block_tables || !out || !workspace) return APT_EINVAL;
+    if (!plan_host || !plan_dev || !q || !block_tables || !out || (!workspace && !static_ws)) return APT_EINVAL;
+    if (static_ws && rs.s.hidden_impl == APT_HIDDEN_ABSORBED) return APT_ESHAPE;
+    if (static_ws) workspace_bytes = APT_STATIC_WORKSPACE_BYTES;
     const int32_t* pw = (const int32_t*)plan_host;
     if (pw[APT_PW_MAGIC] != APT_PLAN_MAGIC) return APT_EINVAL;
     // the plan must have been made for this shape
@@ -1141,12 +1153,9 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
                                             pw[APT_PW_NHIDREQ], hidden_tokens, n_hidden, rs.s.d_model, rs.s.dtype);
     if (workspace_bytes < L.total) return APT_EWORKSPACE;
     // 16-byte vector loads and stores: every base pointer has to be 16-byte aligned
-    if (!aligned16(workspace) || !aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(hidden_pages) ||
+    if ((!static_ws && !aligned16(workspace)) || !aligned16(q) || !aligned16(k_pages) || !aligned16(v_pages) || !aligned16(hidden_pages) ||
         !aligned16(W_K) || !aligned16(W_V) || !aligned16(W_packed) || !aligned16(b_K) || !aligned16(b_V) || !aligned16(plan_dev))
         return APT_EINVAL;
-    const DeviceState* ds = nullptr;
-    rc = device_setup(&ds);
-    if (rc) return rc;
     if (n_hidden < n_items && (!k_pages || !v_pages)) return APT_EINVAL;
     if (n_hidden > 0) {
         if (!hidden_pages || !b_K || !b_V) return APT_EINVAL;
@@ -1155,6 +1164,11 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     }
     int log2_bs = 0;
     while ((1 << log2_bs) < rs.s.block_size) ++log2_bs;
+    // every argument is checked: now the device (first call on a device: its one-off set-up)
+    const DeviceState* ds = nullptr;
+    rc = device_setup(&ds);
+    if (rc) return rc;
+    if (static_ws) workspace = ds->scratch_ptr;
 
     ItemParams p;
     p.plan = (const int32_t*)plan_dev;
@@ -1212,11 +1226,30 @@ extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
+extern "C" int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void* plan_dev,
+                                            const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                            const void* W_K, const void* W_V, const void* W_packed,
+                                            const void* b_K, const void* b_V, const int32_t* block_tables,
+                                            void* out, void* workspace, size_t workspace_bytes, void* stream,
+                                            void* ev_begin, void* ev_end) {
+    return decode_attn(s, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed, b_K, b_V,
+                       block_tables, out, workspace, workspace_bytes, false, stream, ev_begin, ev_end);
+}
+
 extern "C" int apt_hybrid_decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev,
                                       const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
                                       const void* W_K, const void* W_V, const void* W_packed,
                                       const void* b_K, const void* b_V, const int32_t* block_tables,
                                       void* out, void* workspace, size_t workspace_bytes, void* stream) {
-    return apt_hybrid_decode_attn_timed(s, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed,
-                                        b_K, b_V, block_tables, out, workspace, workspace_bytes, stream, nullptr, nullptr);
+    return decode_attn(s, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed, b_K, b_V,
+                       block_tables, out, workspace, workspace_bytes, false, stream, nullptr, nullptr);
+}
+
+extern "C" int apt_hybrid_decode_attn_static(const apt_shape* s, const void* plan_host, void* plan_dev,
+                                             const void* q, const void* k_pages, const void* v_pages, const void* hidden_pages,
+                                             const void* W_K, const void* W_V, const void* W_packed,
+                                             const void* b_K, const void* b_V, const int32_t* block_tables,
+                                             void* out, void* stream) {
+    return decode_attn(s, plan_host, plan_dev, q, k_pages, v_pages, hidden_pages, W_K, W_V, W_packed, b_K, b_V,
+                       block_tables, out, nullptr, 0, true, stream, nullptr, nullptr);
 }

@@ -386,17 +386,22 @@ def run_probe(args):
     else:
         nwg, iters = 1024, 20000
         out = torch.empty(nwg * 256, dtype=torch.float32, device=dev)
-        res = {"probe": "mfma", "flops": nwg * 4 * iters * 16 * 32768.0}
-        for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
-            for _ in range(args.warmup):
-                ab.apt_probe_mfma(out, nwg, iters, rnd, st)
-            a.record()
-            for _ in range(args.steps):
-                ab.apt_probe_mfma(out, nwg, iters, rnd, st)
-            b.record()
-            torch.cuda.synchronize()
-            ms = a.elapsed_time(b) / args.steps
-            res[name] = {"ms": ms, "TFLOPs": res["flops"] / ms / 1e9}
+        res = {"probe": "mfma"}
+        for vname, variant, per_iter in (("f16_32x32x16", 0, 16 * 32768.0), ("f16_16x16x32", 1, 64 * 16384.0),
+                                         ("bf16_32x32x16", 2, 16 * 32768.0), ("bf16_16x16x32", 3, 64 * 16384.0)):
+            its = iters if per_iter < 1e6 else iters // 2
+            flops = nwg * 4 * its * per_iter
+            res[vname] = {"flops": flops}
+            for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+                for _ in range(args.warmup):
+                    ab.apt_probe_mfma(out, nwg, its, rnd, variant, st)
+                a.record()
+                for _ in range(args.steps):
+                    ab.apt_probe_mfma(out, nwg, its, rnd, variant, st)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b) / args.steps
+                res[vname][name] = {"ms": ms, "TFLOPs": flops / ms / 1e9}
         print(json.dumps(res))
 
 

@@ -35,16 +35,16 @@ int apt_hybrid_decode_attn_timed(const apt_shape* s, const void* plan_host, void
 int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* stream);
 
 /*
- * Register-only fp16 MFMA loop (no memory traffic): n_workgroups workgroups of 256
- * threads, each wave issuing iters * 16 independent 32x32x16 MFMAs
- * (n_workgroups * 4 * iters * 16 * 32768 flops in total).  random_operands = 0: constant
- * operands; != 0: operands of magnitude ~1 with random mantissas and signs, which is what
- * the multipliers see with real data (the sustained clock under the board's power limit
- * depends on it).  `out` (device) receives n_workgroups * 256 floats.  Exists to measure the
- * rate the matrix pipes sustain on the device at hand, as context for the MFMA roofline
- * fraction.
+ * Register-only MFMA loop (no memory traffic): n_workgroups workgroups of 256 threads, each wave
+ * holding a 128 x 128 fp32 accumulator tile and issuing per iteration
+ *   variant 0 / 2:  16 independent 32x32x16 MFMAs, fp16 / bf16  (iters * 16 * 32768 flops per wave)
+ *   variant 1 / 3:  64 independent 16x16x32 MFMAs, fp16 / bf16  (iters * 64 * 16384 flops per wave)
+ * random_operands = 0: constant operands; != 0: operands of magnitude ~1 with random mantissas and
+ * signs, which is what the multipliers see with real data (the sustained clock under the board's
+ * power limit depends on it).  `out` (device) receives n_workgroups * 256 floats.  Exists to measure
+ * the rate the matrix pipes sustain on the device at hand, as context for the MFMA roofline fraction.
  */
-int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, void* stream);
+int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, int variant, void* stream);
 
 #ifdef __cplusplus
 }

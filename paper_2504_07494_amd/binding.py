@@ -264,9 +264,9 @@ def apt_copy_bytes(dst, src, nbytes, stream=0):
     _check(lib().apt_copy_bytes(_ptr(dst), _ptr(src), C.c_size_t(nbytes), C.c_void_p(stream)), "apt_copy_bytes")
 
 
-def apt_probe_mfma(out, n_workgroups, iters, random_operands=0, stream=0):
+def apt_probe_mfma(out, n_workgroups, iters, random_operands=0, variant=0, stream=0):
     _check(lib().apt_probe_mfma(_ptr(out), C.c_int(n_workgroups), C.c_int(iters), C.c_int(random_operands),
-                                C.c_void_p(stream)), "apt_probe_mfma")
+                                C.c_int(variant), C.c_void_p(stream)), "apt_probe_mfma")
 
 
 # --- decoding of a plan blob for tests (layout documented in the header) ------------------

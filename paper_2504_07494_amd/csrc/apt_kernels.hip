@@ -901,39 +901,72 @@ __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const ui
     for (; i < n; i += stride) dst[i] = src[i];
 }
 
-// Register-only MFMA loop: 4 waves per workgroup, 16 independent 32x32x16 fp16 MFMAs per
-// iteration and wave, no memory traffic.  Measures the rate the matrix pipes sustain.  With
-// random_operands the 8 operand registers hold values of magnitude ~1 with random mantissas and
-// signs (what real activations look like to the multipliers) instead of constants.
+// Register-only MFMA loop: 4 waves per workgroup, a 128 x 128 accumulator tile per wave (256 registers), no
+// memory traffic.  Measures the rate the matrix pipes sustain.  With random_operands the operand registers
+// hold values of magnitude ~1 with random mantissas and signs (what real activations look like to the
+// multipliers) instead of constants.  VARIANT 0 / 2: 16 independent 32x32x16 MFMAs per iteration (fp16 /
+// bf16); 1 / 3: 64 independent 16x16x32 MFMAs per iteration (fp16 / bf16; twice the flops per iteration).
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <int VARIANT>
 __global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, int iters, int random_operands) {
-    f32x16_t acc[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-    uint4 a[4], b[4];
+    constexpr bool kSmall = (VARIANT & 1) != 0;          // 16x16x32 tiles
+    constexpr int DT = (VARIANT & 2) ? 2 : 1;
+    constexpr int NF = kSmall ? 8 : 4;                   // operand fragments per side
+    uint4 a[NF], b[NF];
     uint32_t x = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u + 12345u);
+    const uint32_t one = DT == 1 ? 0x3c003c00u : 0x3f803f80u, half = DT == 1 ? 0x38003800u : 0x3f003f00u;
+    const uint32_t keep = DT == 1 ? 0x83ff83ffu : 0x807f807fu;      // sign and mantissa bits
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        a[i] = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);
-        b[i] = make_uint4(0x38003800u, 0x38003800u, 0x38003800u, 0x38003800u);
+    for (int i = 0; i < NF; ++i) {
+        a[i] = make_uint4(one, one, one, one);
+        b[i] = make_uint4(half, half, half, half);
         if (random_operands) {
-            auto nxt = [&]() { x ^= x << 13; x ^= x >> 17; x ^= x << 5; return (x & 0x83ff83ffu) | 0x3c003c00u; };
+            auto nxt = [&]() { x ^= x << 13; x ^= x >> 17; x ^= x << 5; return (x & keep) | one; };
             a[i] = make_uint4(nxt(), nxt(), nxt(), nxt());
             b[i] = make_uint4(nxt(), nxt(), nxt(), nxt());
         }
     }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i * 4 + j] = mfma32<1>(a[i], b[j], acc[i * 4 + j]);
-    }
     float sum = 0.f;
+    if constexpr (!kSmall) {
+        f32x16_t acc[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+        for (int i = 0; i < 16; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sum += acc[i][e];
+            for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i * 4 + j] = mfma32<DT>(a[i], b[j], acc[i * 4 + j]);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sum += acc[i][e];
+    } else {
+        f32x4_t acc[64];
+#pragma unroll
+        for (int i = 0; i < 64; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if constexpr (DT == 1)
+                        acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8_t, a[i]),
+                                                                                __builtin_bit_cast(h8_t, b[j]), acc[i * 8 + j], 0, 0, 0);
+                    else
+                        acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8_t, a[i]),
+                                                                                 __builtin_bit_cast(bf8_t, b[j]), acc[i * 8 + j], 0, 0, 0);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 64; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum += acc[i][e];
+    }
     out[(int64_t)blockIdx.x * kThreads + threadIdx.x] = sum;
 }
 
@@ -1117,10 +1150,14 @@ extern "C" int apt_copy_bytes(void* dst, const void* src, size_t bytes, void* st
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
-extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, void* stream) {
-    if (!out || n_workgroups < 1 || iters < 1) return APT_EINVAL;
-    hipLaunchKernelGGL(apt_mfma_probe_kernel, dim3(n_workgroups), dim3(kThreads), 0, (hipStream_t)stream, (float*)out, iters,
-                       random_operands);
+extern "C" int apt_probe_mfma(void* out, int n_workgroups, int iters, int random_operands, int variant, void* stream) {
+    if (!out || n_workgroups < 1 || iters < 1 || variant < 0 || variant > 3) return APT_EINVAL;
+    const dim3 grid(n_workgroups), block(kThreads);
+    hipStream_t st = (hipStream_t)stream;
+    if (variant == 0) hipLaunchKernelGGL(apt_mfma_probe_kernel<0>, grid, block, 0, st, (float*)out, iters, random_operands);
+    else if (variant == 1) hipLaunchKernelGGL(apt_mfma_probe_kernel<1>, grid, block, 0, st, (float*)out, iters, random_operands);
+    else if (variant == 2) hipLaunchKernelGGL(apt_mfma_probe_kernel<2>, grid, block, 0, st, (float*)out, iters, random_operands);
+    else hipLaunchKernelGGL(apt_mfma_probe_kernel<3>, grid, block, 0, st, (float*)out, iters, random_operands);
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 

@@ -31,6 +31,7 @@ constexpr int kThreads = 256;
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 // 16-byte load of data that is read once (streamed past the caches)
@@ -351,20 +352,22 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // hidden-kind items, MFMA version (fp16 / bf16, head_dim 128): persistent workgroups
 // ---------------------------------------------------------------------------------
 // Per item: K_h and V_h of a tile of up to 256 tokens, [256 channels] x [256 tokens] with
-// k = d_model, on v_mfma_f32_32x32x16.  The four waves are (mat, th): mat 0 = K_h channels,
-// mat 1 = V_h channels; th picks the token blocks 2b + th (b = 0..3, 32 tokens each), so a
-// short tile leaves both halves the same number of blocks.  K waves multiply W (rows =
-// channels) by X^T and get D[channel][token]: a lane owns one token per tile column and
-// sums over channels in registers for the score.  V waves multiply X (rows = tokens) by
-// W^T and get D[token][channel]: a lane owns one channel and sums over tokens in registers
-// for the weighted value sum.  Both read the same LDS images; only which image feeds
-// which MFMA operand differs.
+// k = d_model, on v_mfma_f32_16x16x32 (per flop it moves half the accumulator data of the
+// 32x32x16 form, which is what counts on a power-limited chip).  The four waves are (mat, th):
+// mat 0 = K_h channels, mat 1 = V_h channels; th picks the token blocks 2b + th (b = 0..3,
+// 32 tokens each), so a short tile leaves both halves the same number of blocks.  A wave owns a
+// 128 x 128 accumulator tile as 8 x 8 MFMA tiles of 16 x 16.  K waves multiply W (rows =
+// channels) by X^T and get D[channel][token]: a lane owns one token per tile column and sums
+// over channels in registers for the score.  V waves multiply X (rows = tokens) by W^T and get
+// D[token][channel]: a lane owns one channel and sums over tokens in registers for the weighted
+// value sum.  Both read the same LDS images; only which image feeds which MFMA operand differs.
 //
-// k runs in tiles of 32 through four LDS stages, each 16 KB of packed weights (already in
-// LDS order in memory) and 16 KB of X rows, filled by global->LDS copies that bypass
-// registers; up to four k-tiles are in flight or waiting while one is multiplied.  Rows are 64 B; the
-// 16-byte unit c of a row sits at c ^ swz(row), which keeps the row-wise copies and the
-// column-wise operand reads spread over all banks.
+// k runs in tiles of 32 (one MFMA k-step) through four LDS stages, each 16 KB of packed weights
+// (already in LDS order in memory) and 16 KB of X rows, filled by global->LDS copies that bypass
+// registers; up to four k-tiles are in flight or waiting while one is multiplied.  Rows are 64 B;
+// the 16-byte unit c of a row sits at c ^ swz(row), which keeps the row-wise copies and the
+// column-wise operand reads spread over all banks.  The operands of k-tile kt+1 are read into a
+// second register set while k-tile kt is multiplied.
 //
 // A workgroup walks a queue of items (queue = blockIdx % 8, the XCD the workgroup runs
 // on, so that the workgroups sharing an L2 work on few heads and few token tiles at a
@@ -377,8 +380,9 @@ constexpr int kStages = 4;
 constexpr int kMfmaScratch = 4096;                     // epilogue scratch behind the stages
 constexpr int kMfmaLds = 2 * kStages * kTileBytes + kMfmaScratch;
 constexpr int kStageLoads = 8;                         // copies per wave and k-tile: 4 of W, 4 of X
+constexpr int kFragBytes = 16 * kRowBytes;             // the 16 rows of one MFMA operand fragment
 
-// (row >> 2) & 3: measured free of LDS bank conflicts for the 16-byte operand reads of 64-byte rows
+// (row >> 2) & 3: free of LDS bank conflicts for 16-byte operand reads of 16 consecutive 64-byte rows
 __host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
 
 template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
@@ -386,6 +390,13 @@ template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4&
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8_t, a), __builtin_bit_cast(h8_t, b), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
+}
+// A: lane l holds row l % 16, k = 8 (l / 16) .. +7; B: column l % 16, the same k; D: column l % 16, rows 4 (l / 16) + e
+template <int DT> __device__ inline f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+    if constexpr (DT == 1)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8_t, a), __builtin_bit_cast(h8_t, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
 }
 
 // 16-byte global -> LDS copy without a register stage: lane i's 16 bytes land at
@@ -401,11 +412,17 @@ __device__ inline uint4 lds_read16(uint32_t addr) {
 }
 template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// byte offset of operand fragment f inside an LDS image: the W image holds the channels of a wave in order
+// (fragment f = rows 16 f ..), the X image holds the token blocks of a wave interleaved with the other wave's
+// (fragment f = the half f % 2 of the 32-token block f / 2, which sits 64 rows after the previous block)
+__device__ constexpr int w_frag_off(int f) { return f * kFragBytes; }
+__device__ constexpr int x_frag_off(int f) { return (64 * (f >> 1) + 16 * (f & 1)) * kRowBytes; }
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
     constexpr int HD = 128;
     extern __shared__ __align__(16) char lds[];
-    const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mat = w >> 1, th = w & 1;
     const int d = p.d;
@@ -426,24 +443,20 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     float* o_lds = scr + 640;       // [2][128] per-half un-normalised output
     float* ml_lds = scr + 896;      // [2][2] per-half (m, l); [4], [5] = halves of q . b_K
 
-    // Operand slot i of the "A" side is rows a_row + i * a_step, of the "B" side rows
-    // b_row + i * b_step, in the W image (K: A side, V: B side) or the X image.  Unit of
-    // sub-step ks: (2 ks + half) ^ swz(row), so its address is the ks = 0 address ^ (32 ks);
-    // swz does not change with the slot (row steps of 32 and 64).
+    // This lane's 16 bytes of fragment 0, stage 0, in the W image (the channels of this wave) and in the X image
+    // (the token blocks of this wave): row lane % 16 of the fragment, unit (lane / 16) ^ swz(row); swz does not
+    // change from fragment to fragment (their first rows are multiples of 16), so every other fragment and stage
+    // is a constant offset away.
     // (computed per item, right before its k loop: kept across the epilogue they would sit in scratch)
-    uint32_t a_addr[4], b_addr[4];
+    uint32_t w_base, x_base;
 #define APT_OPERAND_ADDRESSES()                                                                             \
     {                                                                                                       \
-        int ln_ = lane, hf_ = half;                                                                         \
-        asm volatile("" : "+v"(ln_), "+v"(hf_));                                                            \
-        const int wrow_ = mat * 128 + (ln_ & 31), xrow_ = th * 32 + (ln_ & 31);                             \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
-            const int wr_ = wrow_ + 32 * i_, xr_ = xrow_ + 64 * i_;                                         \
-            const uint32_t wa_ = lds_base + wr_ * kRowBytes + ((hf_ ^ swz(wr_)) * 16);                      \
-            const uint32_t xa_ = lds_base + kStages * kTileBytes + xr_ * kRowBytes + ((hf_ ^ swz(xr_)) * 16); \
-            a_addr[i_] = mat == 0 ? wa_ : xa_;                                                              \
-            b_addr[i_] = mat == 0 ? xa_ : wa_;                                                              \
-        }                                                                                                   \
+        int ln_ = lane;                                                                                     \
+        asm volatile("" : "+v"(ln_));                                                                       \
+        const int l16_ = ln_ & 15, qd_ = ln_ >> 4;                                                          \
+        const uint32_t off_ = l16_ * kRowBytes + ((qd_ ^ swz(l16_)) * 16);                                  \
+        w_base = lds_base + mat * 128 * kRowBytes + off_;                                                   \
+        x_base = lds_base + kStages * kTileBytes + th * 32 * kRowBytes + off_;                              \
     }
 
     // ---- this workgroup's share of the hidden-kind items
@@ -498,80 +511,64 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         APT_STAGE_FIRST(0, 4)
     }
 
-    f32x16_t acc[4][4];
-    uint4 fa[2][4], fb[2][4];
-#define APT_LOAD_FRAGS(SET, ST, KS, NI, NJ)                                                                 \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                      \
-        if (i_ < NI) fa[SET][i_] = lds_read16((a_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
-        if (i_ < NJ) fb[SET][i_] = lds_read16((b_addr[i_] ^ (32 * (KS))) + (ST) * kTileBytes);              \
-    }
-#define APT_MFMA_ALL(SET, NI, NJ)                                                                           \
-    _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                     \
-        _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                                 \
-            acc[i_][j_] = mfma32<DT>(fa[SET][i_], fb[SET][j_], acc[i_][j_]);                           \
-        }                                                                                                   \
-    }
-    // scheduling hints: interleave the operand reads of the next sub-step with this sub-step's MFMAs
-#define APT_SCHED_STEP(NI, NJ)                                                                              \
+    // acc[i][j]: A-side fragment i (rows) x B-side fragment j (columns).  MAT 0 (K wave): A = W fragments
+    // (NI = 8), B = X fragments (NJ = 2 per valid token block); MAT 1 (V wave): A = X, B = W.
+    // fr[set][..]: the NI A-side fragments, then the NJ B-side fragments of one k-tile.
+    f32x4_t acc[8][8];
+    uint4 fr[2][16];
+    // LDS address of operand slot R (0 .. NI + NJ - 1) in stage 0
+#define APT_SLOT_ADDR(MAT, NI, R)                                                                           \
+    ((MAT) == 0 ? ((R) < (NI) ? w_base + w_frag_off(R) : x_base + x_frag_off((R) - (NI)))                   \
+                : ((R) < (NI) ? x_base + x_frag_off(R) : w_base + w_frag_off((R) - (NI))))
+    // MFMA index of a k-tile (after the operand reads of the next one) in front of which refill copy C is issued
+#define APT_COPY_AT(C, NI, NJ) ((NI) + (NJ) + (C) * ((NI) * (NJ) - (NI) - (NJ)) / kStageLoads)
+    // One k-tile, in stage ST, its operands already in register set ST % 2.  If another k-tile follows: all
+    // waves meet (this wave's copies of the next k-tile have landed: at most WAITN younger copies may still be in
+    // flight; every wave has all operands of THIS k-tile in registers, so its stage is no longer read), then the
+    // next k-tile's operands are read into the other register set, one read per MFMA; after them, spread over the
+    // remaining MFMAs, this stage is refilled with k-tile kt + 4.
+#define APT_K_TILE(ST, STAGE, WAITN, NEXT, MAT, NI, NJ)                                                     \
     {                                                                                                       \
-        _Pragma("unroll") for (int s_ = 0; s_ < NI + NJ; ++s_) {                                            \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                              \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                              \
-        }                                                                                                   \
-        __builtin_amdgcn_sched_group_barrier(0x008, NI * NJ - NI - NJ, 0);                                  \
-    }
-    // one k-tile in stage ST: the first sub-step multiplies while the second one's operands are
-    // read; then all waves meet (their copies of the next k-tile have landed: at most WAITN
-    // younger copies may still be in flight; this k-tile's stage is no longer read, all its
-    // operands are in registers); then the next k-tile's first operands are read and, one copy
-    // per MFMA pair, this stage is refilled with k-tile kt + 4 while the second sub-step multiplies.
-#define APT_K_TILE(ST, STAGE, WAITN, NEXT, NI, NJ)                                                          \
-    {                                                                                                       \
-        APT_LOAD_FRAGS(1, ST, 1, NI, NJ)                                                                    \
-        APT_MFMA_ALL(0, NI, NJ)                                                                             \
-        APT_SCHED_STEP(NI, NJ)                                                                              \
         if (NEXT) {                                                                                         \
             wait_vmcnt<WAITN>();                                                                            \
             __syncthreads();                                                                                \
-            APT_LOAD_FRAGS(0, ((ST) + 1) & 3, 0, NI, NJ)                                                    \
         }                                                                                                   \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
-        _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                 \
-            _Pragma("unroll") for (int j_ = 0; j_ < NJ; ++j_) {                                             \
-                const int m_ = i_ * NJ + j_;              /* 8 copies spread over the NI * NJ MFMAs */      \
-                if (STAGE) {                                                                                \
-                    _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                              \
-                        if (c_ * (NI * NJ) / kStageLoads == m_) stage_chunk(kt + 4, ST, c_);                \
-                }                                                                                           \
-                acc[i_][j_] = mfma32<DT>(fa[1][i_], fb[1][j_], acc[i_][j_]);                           \
-                __builtin_amdgcn_sched_barrier(0);                                                          \
+        _Pragma("unroll") for (int m_ = 0; m_ < (NI) * (NJ); ++m_) {                                        \
+            if (NEXT && m_ < (NI) + (NJ))                                                                   \
+                fr[((ST) + 1) & 1][m_] = lds_read16(APT_SLOT_ADDR(MAT, NI, m_) + (((ST) + 1) & 3) * kTileBytes); \
+            if (STAGE) {                                                                                    \
+                _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                                  \
+                    if (APT_COPY_AT(c_, NI, NJ) == m_) stage_chunk(kt + 4, ST, c_);                         \
             }                                                                                               \
+            acc[m_ / (NJ)][m_ % (NJ)] = mfma16<DT>(fr[(ST) & 1][m_ / (NJ)], fr[(ST) & 1][(NI) + m_ % (NJ)],  \
+                                                   acc[m_ / (NJ)][m_ % (NJ)]);                              \
+            __builtin_amdgcn_sched_barrier(0);                                                              \
         }                                                                                                   \
     }
     // The addresses used inside the k loop must be in registers with nothing pending behind them
     // when the loop starts: a reload the compiler still waits for inside the loop would also wait
     // for the staging copies.
-#define APT_K_LOOP(NI, NJ)                                                                                  \
+#define APT_K_LOOP(MAT, NI, NJ)                                                                             \
     {                                                                                                       \
-        asm volatile("" : "+v"(a_addr[0]), "+v"(a_addr[1]), "+v"(a_addr[2]), "+v"(a_addr[3]),               \
-                          "+v"(b_addr[0]), "+v"(b_addr[1]), "+v"(b_addr[2]), "+v"(b_addr[3]));              \
+        asm volatile("" : "+v"(w_base), "+v"(x_base));                                                      \
         asm volatile("" : "+v"(xsrc[0]), "+v"(xsrc[1]), "+v"(xsrc[2]), "+v"(xsrc[3]), "+v"(wsrc));          \
-        APT_LOAD_FRAGS(0, 0, 0, NI, NJ)                                                                     \
+        _Pragma("unroll") for (int r_ = 0; r_ < (NI) + (NJ); ++r_) fr[0][r_] = lds_read16(APT_SLOT_ADDR(MAT, NI, r_)); \
         int kt = 0;                                                                                         \
         for (; kt + 8 <= nkt; kt += 4) {                                                                    \
-            APT_K_TILE(0, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            APT_K_TILE(0, true, 2 * kStageLoads, true, MAT, NI, NJ)                                         \
             ++kt;                                                                                           \
-            APT_K_TILE(1, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            APT_K_TILE(1, true, 2 * kStageLoads, true, MAT, NI, NJ)                                         \
             ++kt;                                                                                           \
-            APT_K_TILE(2, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            APT_K_TILE(2, true, 2 * kStageLoads, true, MAT, NI, NJ)                                         \
             ++kt;                                                                                           \
-            APT_K_TILE(3, true, 2 * kStageLoads, true, NI, NJ)                                              \
+            APT_K_TILE(3, true, 2 * kStageLoads, true, MAT, NI, NJ)                                         \
             kt -= 3;                                                                                        \
         }                                                                                                   \
-        APT_K_TILE(0, false, 2 * kStageLoads, true, NI, NJ)   /* the last four k-tiles refill nothing */    \
-        APT_K_TILE(1, false, kStageLoads, true, NI, NJ)                                                     \
-        APT_K_TILE(2, false, 0, true, NI, NJ)                                                               \
-        APT_K_TILE(3, false, 0, false, NI, NJ)                                                              \
+        APT_K_TILE(0, false, 2 * kStageLoads, true, MAT, NI, NJ)   /* the last four k-tiles refill nothing */ \
+        APT_K_TILE(1, false, kStageLoads, true, MAT, NI, NJ)                                                \
+        APT_K_TILE(2, false, 0, true, MAT, NI, NJ)                                                          \
+        APT_K_TILE(3, false, 0, false, MAT, NI, NJ)                                                         \
     }
 
     while (have) {
@@ -600,16 +597,16 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         const int nb = (nvb - th + 1) >> 1;
 
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
         APT_OPERAND_ADDRESSES()
         // everything issued so far has to land here: the loads the compiler keeps track of (or the
         // wait counts it would place inside the k loop for them would also wait for the staging
-        // copies) and with them the first three k-tiles
+        // copies) and with them the first four k-tiles
         wait_vmcnt<0>();
 #pragma unroll
         for (int i = 0; i < 4; ++i) asm volatile("" ::"v"(idsn[i]));
@@ -617,15 +614,16 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         __syncthreads();
         // a short tile multiplies only the token blocks that hold valid tokens (at least one, so
         // that every wave runs the same barriers)
-        if (nb == 4) APT_K_LOOP(4, 4)
-        else if (mat == 0) {
-            if (nb == 3) APT_K_LOOP(4, 3)
-            else if (nb == 2) APT_K_LOOP(4, 2)
-            else APT_K_LOOP(4, 1)
+        if (mat == 0) {
+            if (nb == 4) APT_K_LOOP(0, 8, 8)
+            else if (nb == 3) APT_K_LOOP(0, 8, 6)
+            else if (nb == 2) APT_K_LOOP(0, 8, 4)
+            else APT_K_LOOP(0, 8, 2)
         } else {
-            if (nb == 3) APT_K_LOOP(3, 4)
-            else if (nb == 2) APT_K_LOOP(2, 4)
-            else APT_K_LOOP(1, 4)
+            if (nb == 4) APT_K_LOOP(1, 8, 8)
+            else if (nb == 3) APT_K_LOOP(1, 6, 8)
+            else if (nb == 2) APT_K_LOOP(1, 4, 8)
+            else APT_K_LOOP(1, 2, 8)
         }
 
         // stages 0..2 are free now (every wave has passed the last barrier of the k loop; stage 3
@@ -636,77 +634,76 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             APT_STAGE_FIRST(0, 3)
         }
 
-        // ---- epilogue.  Register e of tile (i, j): row 8 (e/4) + 4 half + e%4 of the A-side
-        // block i, column lane%32 of the B-side block j.
+        // ---- epilogue.  Register e of tile (i, j): row 4 (lane / 16) + e of the A-side fragment i,
+        // column lane % 16 of the B-side fragment j.
         // lane-dependent LDS addresses of the epilogue are rebuilt here from values the compiler cannot see
         // through: hoisted out of the item loop they would stay live across the k loops and end up in scratch
-        int ln = lane, hf = half, td = tid;
-        asm volatile("" : "+v"(ln), "+v"(hf), "+v"(td));
+        int ln = lane, td = tid;
+        asm volatile("" : "+v"(ln), "+v"(td));
+        const int l16 = ln & 15, qd = ln >> 4;
         if (mat == 0) {
-            // K wave: rows = channels 32 i + ..., columns = tokens of block 2 j + th
+            // K wave: rows = channels 16 i + 4 qd + e, columns = tokens of X fragment j
             const float qb = ml_lds[4] + ml_lds[5];
-            float sp[4] = {0.f, 0.f, 0.f, 0.f};
+            float sp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 8; ++i) {
+                const float4 q4 = *(const float4*)(qs_lds + 16 * i + 4 * qd);
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const float4 q4 = *(const float4*)(qs_lds + 32 * i + 8 * e4 + 4 * hf);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        sp[j] = fmaf(acc[i][j][4 * e4 + 0], q4.x, sp[j]);
-                        sp[j] = fmaf(acc[i][j][4 * e4 + 1], q4.y, sp[j]);
-                        sp[j] = fmaf(acc[i][j][4 * e4 + 2], q4.z, sp[j]);
-                        sp[j] = fmaf(acc[i][j][4 * e4 + 3], q4.w, sp[j]);
-                    }
-                    // the accumulators are read out of the AGPRs in small groups: read all at once they
-                    // push every long-lived value into scratch, and a scratch reload waits for the copies
-                    // of the next item's k-tiles that are in flight here
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int j = 0; j < 8; ++j) {
+                    sp[j] = fmaf(acc[i][j][0], q4.x, sp[j]);
+                    sp[j] = fmaf(acc[i][j][1], q4.y, sp[j]);
+                    sp[j] = fmaf(acc[i][j][2], q4.z, sp[j]);
+                    sp[j] = fmaf(acc[i][j][3], q4.w, sp[j]);
                 }
+                // the accumulators are read out of the AGPRs in small groups: read all at once they
+                // push every long-lived value into scratch, and a scratch reload waits for the copies
+                // of the next item's k-tiles that are in flight here
+                __builtin_amdgcn_sched_barrier(0);
+            }
             float m = kSentinel;
-            bool ok[4];
+            bool ok[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 8; ++j) {
+                sp[j] += __shfl_xor(sp[j], 16);
                 sp[j] += __shfl_xor(sp[j], 32);
-                ok[j] = (2 * j + th) * 32 + (ln & 31) < nvalid;
+                ok[j] = th * 32 + 64 * (j >> 1) + 16 * (j & 1) + l16 < nvalid;
                 sp[j] = ok[j] ? sp[j] + qb : kSentinel;
                 m = fmaxf(m, sp[j]);
             }
-            m = group_max<32>(m);
+            m = group_max<16>(m);                     // the four lane groups hold the same scores
             float l = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 8; ++j) {
                 const float pw = ok[j] ? fast_exp2(sp[j] - m) : 0.f;
                 l += pw;
-                if (ln < 32) p_lds[(2 * j + th) * 32 + ln] = pw;
+                if (qd == 0) p_lds[th * 32 + 64 * (j >> 1) + 16 * (j & 1) + l16] = pw;
             }
-            l = group_sum<32>(l);
+            l = group_sum<16>(l);
             if (ln == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
         }
         __syncthreads();
         if (have_next) APT_STAGE_FIRST(3, 4)      // every wave has left the k loop: stage 3 is free too
         if (mat == 1) {
-            // V wave: rows = tokens of block 2 i + th, columns = channels 32 j + lane%32
-            float o[4] = {0.f, 0.f, 0.f, 0.f};
+            // V wave: rows = tokens 4 qd + e of X fragment i, columns = channels 16 j + lane % 16
+            float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 8; ++i) {
+                const float4 p4 = *(const float4*)(p_lds + th * 32 + 64 * (i >> 1) + 16 * (i & 1) + 4 * qd);
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const float4 p4 = *(const float4*)(p_lds + (2 * i + th) * 32 + 8 * e4 + 4 * hf);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        o[j] = fmaf(acc[i][j][4 * e4 + 0], p4.x, o[j]);
-                        o[j] = fmaf(acc[i][j][4 * e4 + 1], p4.y, o[j]);
-                        o[j] = fmaf(acc[i][j][4 * e4 + 2], p4.z, o[j]);
-                        o[j] = fmaf(acc[i][j][4 * e4 + 3], p4.w, o[j]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int j = 0; j < 8; ++j) {
+                    o[j] = fmaf(acc[i][j][0], p4.x, o[j]);
+                    o[j] = fmaf(acc[i][j][1], p4.y, o[j]);
+                    o[j] = fmaf(acc[i][j][2], p4.z, o[j]);
+                    o[j] = fmaf(acc[i][j][3], p4.w, o[j]);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             const float l = ml_lds[th * 2 + 1];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 8; ++j) {
+                o[j] += __shfl_xor(o[j], 16);
                 o[j] += __shfl_xor(o[j], 32);
-                if (ln < 32) o_lds[th * 128 + 32 * j + ln] = fmaf(l, bv_lds[32 * j + ln], o[j]);
+                if (qd == 0) o_lds[th * 128 + 16 * j + l16] = fmaf(l, bv_lds[16 * j + l16], o[j]);
             }
         }
         __syncthreads();
@@ -724,9 +721,8 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     }
 #undef APT_K_LOOP
 #undef APT_K_TILE
-#undef APT_SCHED_STEP
-#undef APT_MFMA_ALL
-#undef APT_LOAD_FRAGS
+#undef APT_COPY_AT
+#undef APT_SLOT_ADDR
 #undef APT_STAGE_FIRST
 #undef APT_OPERAND_ADDRESSES
 #undef APT_MAKE_SOURCES
@@ -906,7 +902,6 @@ __global__ __launch_bounds__(kThreads) void apt_copy_kernel(uint4* dst, const ui
 // hold values of magnitude ~1 with random mantissas and signs (what real activations look like to the
 // multipliers) instead of constants.  VARIANT 0 / 2: 16 independent 32x32x16 MFMAs per iteration (fp16 /
 // bf16); 1 / 3: 64 independent 16x16x32 MFMAs per iteration (fp16 / bf16; twice the flops per iteration).
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int VARIANT>
 __global__ __launch_bounds__(kThreads) void apt_mfma_probe_kernel(float* out, int iters, int random_operands) {
     constexpr bool kSmall = (VARIANT & 1) != 0;          // 16x16x32 tiles

@@ -351,19 +351,23 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // ---------------------------------------------------------------------------------
 // hidden-kind items, MFMA version (fp16 / bf16, head_dim 128): persistent workgroups
 // ---------------------------------------------------------------------------------
-// Per item: K_h and V_h of a tile of up to 256 tokens, [256 channels] x [256 tokens] with
-// k = d_model, on v_mfma_f32_16x16x32 (per flop it moves half the accumulator data of the
-// 32x32x16 form, which is what counts on a power-limited chip).  The four waves are (mat, th):
-// mat 0 = K_h channels, mat 1 = V_h channels; th picks the token blocks 2b + th (b = 0..3,
-// 32 tokens each), so a short tile leaves both halves the same number of blocks.  A wave owns a
-// 128 x 128 accumulator tile as 8 x 8 MFMA tiles of 16 x 16.  K waves multiply W (rows =
-// channels) by X^T and get D[channel][token]: a lane owns one token per tile column and sums
-// over channels in registers for the score.  V waves multiply X (rows = tokens) by W^T and get
-// D[token][channel]: a lane owns one channel and sums over tokens in registers for the weighted
-// value sum.  Both read the same LDS images; only which image feeds which MFMA operand differs.
+// Per item: K_h and V_h of a tile of up to kTokTile = 320 tokens, [256 channels] x [320 tokens] with
+// k = d_model, on v_mfma_f32_16x16x32.  The four waves are (mat, th): mat 0 = K_h channels, mat 1 =
+// V_h channels; th picks the token blocks 2b + th (b = 0..4, 32 tokens each), so a short tile leaves
+// both halves the same number of blocks.  A wave owns a 128 x 160 accumulator tile as 8 x 10 MFMA
+// tiles of 16 x 16: 320 registers, more than the 256 AGPRs, so part of it lives in ordinary VGPRs.
+// The tile is as large as the register file allows because the kernel is bound by the L2 -> LDS
+// copies as much as by the matrix pipes: per k-tile a workgroup copies (256 + 320) rows of 64 B for
+// 256 x 320 x 32 multiply-adds, 10 % fewer bytes per flop than a 256 x 256 tile, and a k-tile lasts
+// 25 % longer, which is that much more latency the four stages can cover.
+// K waves multiply W (rows = channels) by X^T and get D[channel][token]: a lane owns one token per
+// tile column and sums over channels in registers for the score.  V waves multiply X (rows =
+// tokens) by W^T and get D[token][channel]: a lane owns one channel and sums over tokens in
+// registers for the weighted value sum.  Both read the same LDS images; only which image feeds
+// which MFMA operand differs.
 //
 // k runs in tiles of 32 (one MFMA k-step) through four LDS stages, each 16 KB of packed weights
-// (already in LDS order in memory) and 16 KB of X rows, filled by global->LDS copies that bypass
+// (already in LDS order in memory) and 20 KB of X rows, filled by global->LDS copies that bypass
 // registers; up to four k-tiles are in flight or waiting while one is multiplied.  Rows are 64 B;
 // the 16-byte unit c of a row sits at c ^ swz(row), which keeps the row-wise copies and the
 // column-wise operand reads spread over all banks.  The operands of k-tile kt+1 are read into a
@@ -375,12 +379,18 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // k-tiles of the next item are already on their way into LDS.
 constexpr int kBK = 32;
 constexpr int kRowBytes = kBK * 2;                     // 64 B
-constexpr int kTileBytes = 256 * kRowBytes;            // 16 KB
+constexpr int kTokFrags = APT_MFMA_HIDDEN_CHUNK / 32;  // X fragments (16 tokens) per wave: 10
+constexpr int kTokTile = 32 * kTokFrags;               // token rows of a tile: 320
+constexpr int kXChunks = kTokTile / 64;                // 1 KB copies of X rows per wave and k-tile: 5
+constexpr int kWTileBytes = 256 * kRowBytes;           // 16 KB
+constexpr int kXTileBytes = kTokTile * kRowBytes;      // 20 KB
 constexpr int kStages = 4;
-constexpr int kMfmaScratch = 4096;                     // epilogue scratch behind the stages
-constexpr int kMfmaLds = 2 * kStages * kTileBytes + kMfmaScratch;
-constexpr int kStageLoads = 8;                         // copies per wave and k-tile: 4 of W, 4 of X
+constexpr int kXImage = kStages * kWTileBytes;         // LDS offset of the X stages
+constexpr int kMfmaScratch = 5120;                     // epilogue scratch behind the stages
+constexpr int kMfmaLds = kStages * (kWTileBytes + kXTileBytes) + kMfmaScratch;
+constexpr int kStageLoads = 4 + kXChunks;              // copies per wave and k-tile: 4 of W, 5 of X
 constexpr int kFragBytes = 16 * kRowBytes;             // the 16 rows of one MFMA operand fragment
+static_assert(kTokTile % 64 == 0 && kMfmaLds <= 160 * 1024, "tile does not fit");
 
 // (row >> 2) & 3: free of LDS bank conflicts for 16-byte operand reads of 16 consecutive 64-byte rows
 __host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
@@ -399,10 +409,25 @@ template <int DT> __device__ inline f32x4_t mfma16(const uint4& a, const uint4& 
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8_t, a), __builtin_bit_cast(bf8_t, b), c, 0, 0, 0);
 }
 
+// The same MFMA with its accumulator in ordinary VGPRs.  The compiler keeps every accumulator of a kernel in one
+// register class (here the 256 AGPRs); the tiles beyond those are accumulated through this form.  Its operands are
+// tracked like any other instruction's (wait counts for the LDS reads that feed it); successive uses of one
+// accumulator are a whole k-tile apart.
+template <int DT> __device__ inline void mfma16_vgpr(const uint4& a, const uint4& b, f32x4_t& c) {
+    const u32x4_t av = __builtin_bit_cast(u32x4_t, a), bv = __builtin_bit_cast(u32x4_t, b);
+    if constexpr (DT == 1) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(c) : "v"(av), "v"(bv));
+    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(av), "v"(bv));
+}
+
 // 16-byte global -> LDS copy without a register stage: lane i's 16 bytes land at
 // lds_addr + 16 i.  The LDS address goes through M0 and must be wave-uniform.
 __device__ inline void gload_lds16(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
+}
+// The same with a wave-uniform 64-bit base and a 32-bit byte offset per lane.
+__device__ inline void gload_lds16_base(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base)
+                 : "memory", "m0");
 }
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4_t;
 // 16-byte LDS read at an absolute LDS address (the dynamic LDS base is folded into the operand addresses once)
@@ -417,6 +442,8 @@ template <int N> __device__ inline void wait_vmcnt() { asm volatile("s_waitcnt v
 // (fragment f = the half f % 2 of the 32-token block f / 2, which sits 64 rows after the previous block)
 __device__ constexpr int w_frag_off(int f) { return f * kFragBytes; }
 __device__ constexpr int x_frag_off(int f) { return (64 * (f >> 1) + 16 * (f & 1)) * kRowBytes; }
+// token row (within the tile) of the first token of X fragment f of the wave with token half th
+__device__ inline int x_frag_row(int th, int f) { return th * 32 + 64 * (f >> 1) + 16 * (f & 1); }
 
 template <int DT>
 __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
@@ -434,14 +461,15 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     const int32_t* split_count = p.plan + APT_PW_HEADER;
     const int32_t* ws_offset = split_count + p.B;
 
-    // ---- LDS layout: W stages 0..3 (16 KB each), X stages 0..3, then the epilogue scratch
-    float* scr = (float*)(lds + 2 * kStages * kTileBytes);
-    float* p_lds = scr;             // [256] softmax weights of the tile (per half, relative to its maximum)
-    float* qs_lds = scr + 256;      // [128] q * scale * log2(e)
-    float* bk_lds = scr + 384;      // [128]
-    float* bv_lds = scr + 512;      // [128]
-    float* o_lds = scr + 640;       // [2][128] per-half un-normalised output
-    float* ml_lds = scr + 896;      // [2][2] per-half (m, l); [4], [5] = halves of q . b_K
+    // ---- LDS layout: W stages 0..3 (16 KB each), X stages 0..3 (20 KB each), then the epilogue scratch
+    float* scr = (float*)(lds + kStages * (kWTileBytes + kXTileBytes));
+    float* p_lds = scr;                     // [kTokTile] softmax weights of the tile (per half, relative to its maximum)
+    float* qs_lds = scr + kTokTile;         // [128] q * scale * log2(e)
+    float* bk_lds = qs_lds + 128;           // [128]
+    float* bv_lds = bk_lds + 128;           // [128]
+    float* o_lds = bv_lds + 128;            // [2][128] per-half un-normalised output
+    float* ml_lds = o_lds + 256;            // [2][2] per-half (m, l); [4], [5] = halves of q . b_K
+    static_assert((kTokTile + 3 * 128 + 256 + 8) * 4 <= kMfmaScratch, "epilogue scratch too small");
 
     // This lane's 16 bytes of fragment 0, stage 0, in the W image (the channels of this wave) and in the X image
     // (the token blocks of this wave): row lane % 16 of the fragment, unit (lane / 16) ^ swz(row); swz does not
@@ -456,7 +484,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         const int l16_ = ln_ & 15, qd_ = ln_ >> 4;                                                          \
         const uint32_t off_ = l16_ * kRowBytes + ((qd_ ^ swz(l16_)) * 16);                                  \
         w_base = lds_base + mat * 128 * kRowBytes + off_;                                                   \
-        x_base = lds_base + kStages * kTileBytes + th * 32 * kRowBytes + off_;                              \
+        x_base = lds_base + kXImage + th * 32 * kRowBytes + off_;                                           \
     }
 
     // ---- this workgroup's share of the hidden-kind items
@@ -465,38 +493,39 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     const int q_end = p.plan[APT_PW_QUEUE0 + (g & 7) + 1];
     int qi = p.plan[APT_PW_QUEUE0 + (g & 7)] + (g >> 3);
 
-    // per-lane state of an item: 4 X row sources.  An X chunk of 1 KB is 16 rows; wave w
+    // per-lane state of an item: kXChunks X row sources.  An X chunk of 1 KB is 16 rows; wave w
     // copies chunks w + 4 i: row 16 w + lane/4 + 64 i, LDS unit lane%4 = global unit (lane%4) ^ swz(row)
     const int pu = lane & 3, r0 = 16 * w + (lane >> 2);
     int4 it = make_int4(0, 0, 0, 1);
-    int32_t ids[4];
-    auto lookup = [&](const int4& item, int32_t* out) {       // block ids of this lane's 4 rows
+    int32_t ids[kXChunks];
+    auto lookup = [&](const int4& item, int32_t* out) {       // block ids of this lane's rows
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kXChunks; ++i) {
             int tok = item.z + r0 + 64 * i;
             tok = tok < item.w ? tok : item.w - 1;            // rows past the range repeat the last token (masked later)
             out[i] = p.block_tables[(int64_t)item.x * 2 * p.max_blocks + (tok >> p.log2_bs)];
         }
     };
-    const char* xsrc[4];
+    uint32_t xsrc[kXChunks];                                  // offsets from hidden_pages in 16-byte units
     const char* wsrc = nullptr;
 #define APT_MAKE_SOURCES(XS, WS, ITEM, BLK)                                                                 \
     {                                                                                                       \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                  \
+        _Pragma("unroll") for (int i_ = 0; i_ < kXChunks; ++i_) {                                           \
             const int row_ = r0 + 64 * i_;                                                                  \
             int tok_ = (ITEM).z + row_;                                                                     \
             tok_ = tok_ < (ITEM).w ? tok_ : (ITEM).w - 1;                                                   \
-            XS[i_] = p.hidden_pages + (int64_t)BLK[i_] * blk_bytes + ((int64_t)(tok_ & (p.bs - 1)) * d) * 2 + \
-                     ((pu ^ swz(row_)) * 16);                                                               \
+            XS[i_] = (uint32_t)(((int64_t)BLK[i_] * blk_bytes + ((int64_t)(tok_ & (p.bs - 1)) * d) * 2) >> 4) + \
+                     (pu ^ swz(row_));                                                                      \
         }                                                                                                   \
-        WS = p.W_packed + (int64_t)(ITEM).y * nkt * kTileBytes + w * 1024 + lane * 16;                      \
+        WS = p.W_packed + (int64_t)(ITEM).y * nkt * kWTileBytes + w * 1024 + lane * 16;                     \
     }
-    // copies chunk j (0..3: weights, 4..7: X rows) of this wave's share of k-tile kt into stage st
+    // copies chunk j (0..3: weights, 4..: X rows) of this wave's share of k-tile kt into stage st
     auto stage_chunk = [&](int kt, int st, int j) {
         if (j < 4)
-            gload_lds16(wsrc + (int64_t)kt * kTileBytes + j * 4096, lds_w + st * kTileBytes + j * 4096);
+            gload_lds16(wsrc + (int64_t)kt * kWTileBytes + j * 4096, lds_w + st * kWTileBytes + j * 4096);
         else
-            gload_lds16(xsrc[j - 4] + kt * kRowBytes, lds_w + (kStages + st) * kTileBytes + (j - 4) * 4096);
+            gload_lds16(p.hidden_pages + (uint64_t)xsrc[j - 4] * 16 + kt * kRowBytes,
+                        lds_w + kXImage + st * kXTileBytes + (j - 4) * 4096);
     };
 #define APT_STAGE_FIRST(T0, T1)                                                                             \
     _Pragma("unroll") for (int t_ = (T0); t_ < (T1); ++t_) {                                                \
@@ -511,15 +540,26 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         APT_STAGE_FIRST(0, 4)
     }
 
-    // acc[i][j]: A-side fragment i (rows) x B-side fragment j (columns).  MAT 0 (K wave): A = W fragments
-    // (NI = 8), B = X fragments (NJ = 2 per valid token block); MAT 1 (V wave): A = X, B = W.
+    // Accumulator tile (i, j): A-side fragment i (rows) x B-side fragment j (columns).  MAT 0 (K wave): A = W
+    // fragments (NI = 8), B = X fragments (NJ = 2 per valid token block); MAT 1 (V wave): A = X, B = W.  The 64
+    // tiles of the first 8 X fragments live in AGPRs (acc_a), the 16 tiles of X fragments 8 and 9 (the fifth
+    // token block of the wave) in VGPRs (acc_v).
+    f32x4_t acc_a[64], acc_v[8 * (kTokFrags - 8)];
     // fr[set][..]: the NI A-side fragments, then the NJ B-side fragments of one k-tile.
-    f32x4_t acc[8][8];
-    uint4 fr[2][16];
-    // LDS address of operand slot R (0 .. NI + NJ - 1) in stage 0
-#define APT_SLOT_ADDR(MAT, NI, R)                                                                           \
-    ((MAT) == 0 ? ((R) < (NI) ? w_base + w_frag_off(R) : x_base + x_frag_off((R) - (NI)))                   \
-                : ((R) < (NI) ? x_base + x_frag_off(R) : w_base + w_frag_off((R) - (NI))))
+    uint4 fr[2][8 + kTokFrags];
+    // X fragment and W fragment of tile (I, J)
+#define APT_XF(MAT, I, J) ((MAT) == 0 ? (J) : (I))
+#define APT_WF(MAT, I, J) ((MAT) == 0 ? (I) : (J))
+    // (indices are clamped so that the branch not taken never names an element outside its array)
+#define APT_ACC_A_SAFE(MAT, I, J) acc_a[APT_XF(MAT, I, J) < 8 ? (I) * 8 + (J) : 0]
+#define APT_ACC_V_SAFE(MAT, I, J) acc_v[APT_XF(MAT, I, J) < 8 ? 0 : (APT_XF(MAT, I, J) - 8) * 8 + APT_WF(MAT, I, J)]
+#define APT_ACC_GET(MAT, I, J) (APT_XF(MAT, I, J) < 8 ? APT_ACC_A_SAFE(MAT, I, J) : APT_ACC_V_SAFE(MAT, I, J))
+    // LDS address of operand slot R (0 .. NI + NJ - 1) in stage ST
+#define APT_SLOT_ADDR(MAT, NI, R, ST)                                                                       \
+    ((MAT) == 0 ? ((R) < (NI) ? w_base + w_frag_off(R) + (ST) * kWTileBytes                                 \
+                              : x_base + x_frag_off((R) - (NI)) + (ST) * kXTileBytes)                       \
+                : ((R) < (NI) ? x_base + x_frag_off(R) + (ST) * kXTileBytes                                 \
+                              : w_base + w_frag_off((R) - (NI)) + (ST) * kWTileBytes))
     // MFMA index of a k-tile (after the operand reads of the next one) in front of which refill copy C is issued
 #define APT_COPY_AT(C, NI, NJ) ((NI) + (NJ) + (C) * ((NI) * (NJ) - (NI) - (NJ)) / kStageLoads)
     // One k-tile, in stage ST, its operands already in register set ST % 2.  If another k-tile follows: all
@@ -536,13 +576,18 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         __builtin_amdgcn_sched_barrier(0);                                                                  \
         _Pragma("unroll") for (int m_ = 0; m_ < (NI) * (NJ); ++m_) {                                        \
             if (NEXT && m_ < (NI) + (NJ))                                                                   \
-                fr[((ST) + 1) & 1][m_] = lds_read16(APT_SLOT_ADDR(MAT, NI, m_) + (((ST) + 1) & 3) * kTileBytes); \
+                fr[((ST) + 1) & 1][m_] = lds_read16(APT_SLOT_ADDR(MAT, NI, m_, ((ST) + 1) & 3));            \
             if (STAGE) {                                                                                    \
                 _Pragma("unroll") for (int c_ = 0; c_ < kStageLoads; ++c_)                                  \
                     if (APT_COPY_AT(c_, NI, NJ) == m_) stage_chunk(kt + 4, ST, c_);                         \
             }                                                                                               \
-            acc[m_ / (NJ)][m_ % (NJ)] = mfma16<DT>(fr[(ST) & 1][m_ / (NJ)], fr[(ST) & 1][(NI) + m_ % (NJ)],  \
-                                                   acc[m_ / (NJ)][m_ % (NJ)]);                              \
+            if (APT_XF(MAT, m_ / (NJ), m_ % (NJ)) < 8)                                                      \
+                APT_ACC_A_SAFE(MAT, m_ / (NJ), m_ % (NJ)) =                                                 \
+                    mfma16<DT>(fr[(ST) & 1][m_ / (NJ)], fr[(ST) & 1][(NI) + m_ % (NJ)],                     \
+                               APT_ACC_A_SAFE(MAT, m_ / (NJ), m_ % (NJ)));                                  \
+            else                                                                                            \
+                mfma16_vgpr<DT>(fr[(ST) & 1][m_ / (NJ)], fr[(ST) & 1][(NI) + m_ % (NJ)],                    \
+                                APT_ACC_V_SAFE(MAT, m_ / (NJ), m_ % (NJ)));                                 \
             __builtin_amdgcn_sched_barrier(0);                                                              \
         }                                                                                                   \
     }
@@ -552,8 +597,9 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #define APT_K_LOOP(MAT, NI, NJ)                                                                             \
     {                                                                                                       \
         asm volatile("" : "+v"(w_base), "+v"(x_base));                                                      \
-        asm volatile("" : "+v"(xsrc[0]), "+v"(xsrc[1]), "+v"(xsrc[2]), "+v"(xsrc[3]), "+v"(wsrc));          \
-        _Pragma("unroll") for (int r_ = 0; r_ < (NI) + (NJ); ++r_) fr[0][r_] = lds_read16(APT_SLOT_ADDR(MAT, NI, r_)); \
+        _Pragma("unroll") for (int i_ = 0; i_ < kXChunks; ++i_) asm volatile("" : "+v"(xsrc[i_]));          \
+        asm volatile("" : "+v"(wsrc));                                                                      \
+        _Pragma("unroll") for (int r_ = 0; r_ < (NI) + (NJ); ++r_) fr[0][r_] = lds_read16(APT_SLOT_ADDR(MAT, NI, r_, 0)); \
         int kt = 0;                                                                                         \
         for (; kt + 8 <= nkt; kt += 4) {                                                                    \
             APT_K_TILE(0, true, 2 * kStageLoads, true, MAT, NI, NJ)                                         \
@@ -577,7 +623,9 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         const int nqi = qi + wpx;
         const bool have_next = nqi < q_end;
         int4 itn = it;
-        int32_t idsn[4] = {0, 0, 0, 0};
+        int32_t idsn[kXChunks];
+#pragma unroll
+        for (int i = 0; i < kXChunks; ++i) idsn[i] = 0;
         if (have_next) {
             itn = items[nqi];
             lookup(itn, idsn);
@@ -597,11 +645,13 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         const int nb = (nvb - th + 1) >> 1;
 
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 64; ++i)
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int e = 0; e < 4; ++e) acc_a[i][e] = 0.f;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+        for (int i = 0; i < 8 * (kTokFrags - 8); ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc_v[i][e] = 0.f;
 
         APT_OPERAND_ADDRESSES()
         // everything issued so far has to land here: the loads the compiler keeps track of (or the
@@ -609,18 +659,21 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         // copies) and with them the first four k-tiles
         wait_vmcnt<0>();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) asm volatile("" ::"v"(idsn[i]));
+        for (int i = 0; i < kXChunks; ++i) asm volatile("" ::"v"(idsn[i]));
         asm volatile("" ::"v"(itn.x), "v"(itn.y), "v"(itn.z), "v"(itn.w));
         __syncthreads();
         // a short tile multiplies only the token blocks that hold valid tokens (at least one, so
         // that every wave runs the same barriers)
+        static_assert(kTokFrags == 10, "the dispatch below lists the block counts of a 320-token tile");
         if (mat == 0) {
-            if (nb == 4) APT_K_LOOP(0, 8, 8)
+            if (nb == 5) APT_K_LOOP(0, 8, 10)
+            else if (nb == 4) APT_K_LOOP(0, 8, 8)
             else if (nb == 3) APT_K_LOOP(0, 8, 6)
             else if (nb == 2) APT_K_LOOP(0, 8, 4)
             else APT_K_LOOP(0, 8, 2)
         } else {
-            if (nb == 4) APT_K_LOOP(1, 8, 8)
+            if (nb == 5) APT_K_LOOP(1, 10, 8)
+            else if (nb == 4) APT_K_LOOP(1, 8, 8)
             else if (nb == 3) APT_K_LOOP(1, 6, 8)
             else if (nb == 2) APT_K_LOOP(1, 4, 8)
             else APT_K_LOOP(1, 2, 8)
@@ -644,39 +697,42 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         if (mat == 0) {
             // K wave: rows = channels 16 i + 4 qd + e, columns = tokens of X fragment j
             const float qb = ml_lds[4] + ml_lds[5];
-            float sp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            float sp[kTokFrags];
+#pragma unroll
+            for (int j = 0; j < kTokFrags; ++j) sp[j] = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const float4 q4 = *(const float4*)(qs_lds + 16 * i + 4 * qd);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    sp[j] = fmaf(acc[i][j][0], q4.x, sp[j]);
-                    sp[j] = fmaf(acc[i][j][1], q4.y, sp[j]);
-                    sp[j] = fmaf(acc[i][j][2], q4.z, sp[j]);
-                    sp[j] = fmaf(acc[i][j][3], q4.w, sp[j]);
+                for (int j = 0; j < kTokFrags; ++j) {
+                    const f32x4_t t = APT_ACC_GET(0, i, j);
+                    sp[j] = fmaf(t[0], q4.x, sp[j]);
+                    sp[j] = fmaf(t[1], q4.y, sp[j]);
+                    sp[j] = fmaf(t[2], q4.z, sp[j]);
+                    sp[j] = fmaf(t[3], q4.w, sp[j]);
                 }
-                // the accumulators are read out of the AGPRs in small groups: read all at once they
-                // push every long-lived value into scratch, and a scratch reload waits for the copies
-                // of the next item's k-tiles that are in flight here
+                // the accumulators are read out in small groups: read all at once they push every
+                // long-lived value into scratch, and a scratch reload waits for the copies of the
+                // next item's k-tiles that are in flight here
                 __builtin_amdgcn_sched_barrier(0);
             }
             float m = kSentinel;
-            bool ok[8];
+            bool ok[kTokFrags];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kTokFrags; ++j) {
                 sp[j] += __shfl_xor(sp[j], 16);
                 sp[j] += __shfl_xor(sp[j], 32);
-                ok[j] = th * 32 + 64 * (j >> 1) + 16 * (j & 1) + l16 < nvalid;
+                ok[j] = x_frag_row(th, j) + l16 < nvalid;
                 sp[j] = ok[j] ? sp[j] + qb : kSentinel;
                 m = fmaxf(m, sp[j]);
             }
             m = group_max<16>(m);                     // the four lane groups hold the same scores
             float l = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kTokFrags; ++j) {
                 const float pw = ok[j] ? fast_exp2(sp[j] - m) : 0.f;
                 l += pw;
-                if (qd == 0) p_lds[th * 32 + 64 * (j >> 1) + 16 * (j & 1) + l16] = pw;
+                if (qd == 0) p_lds[x_frag_row(th, j) + l16] = pw;
             }
             l = group_sum<16>(l);
             if (ln == 0) { ml_lds[th * 2] = m; ml_lds[th * 2 + 1] = l; }
@@ -687,14 +743,15 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             // V wave: rows = tokens 4 qd + e of X fragment i, columns = channels 16 j + lane % 16
             float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float4 p4 = *(const float4*)(p_lds + th * 32 + 64 * (i >> 1) + 16 * (i & 1) + 4 * qd);
+            for (int i = 0; i < kTokFrags; ++i) {
+                const float4 p4 = *(const float4*)(p_lds + x_frag_row(th, i) + 4 * qd);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    o[j] = fmaf(acc[i][j][0], p4.x, o[j]);
-                    o[j] = fmaf(acc[i][j][1], p4.y, o[j]);
-                    o[j] = fmaf(acc[i][j][2], p4.z, o[j]);
-                    o[j] = fmaf(acc[i][j][3], p4.w, o[j]);
+                    const f32x4_t t = APT_ACC_GET(1, i, j);
+                    o[j] = fmaf(t[0], p4.x, o[j]);
+                    o[j] = fmaf(t[1], p4.y, o[j]);
+                    o[j] = fmaf(t[2], p4.z, o[j]);
+                    o[j] = fmaf(t[3], p4.w, o[j]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -723,6 +780,11 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
 #undef APT_K_TILE
 #undef APT_COPY_AT
 #undef APT_SLOT_ADDR
+#undef APT_ACC_GET
+#undef APT_ACC_V_SAFE
+#undef APT_ACC_A_SAFE
+#undef APT_WF
+#undef APT_XF
 #undef APT_STAGE_FIRST
 #undef APT_OPERAND_ADDRESSES
 #undef APT_MAKE_SOURCES
@@ -730,7 +792,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     // ---- then a share of the KV-kind items, longest first
     __syncthreads();
     // handed out one by one, so that workgroups that finish their hidden-kind share early take more
-    int* ticket_lds = (int*)(lds + 2 * kStages * kTileBytes);
+    int* ticket_lds = (int*)(lds + kStages * (kWTileBytes + kXTileBytes));
     for (;;) {
         if (tid == 0) *ticket_lds = atomicAdd(p.kv_ticket, 1);
         __syncthreads();

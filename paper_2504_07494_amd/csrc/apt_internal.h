@@ -35,7 +35,9 @@ enum {
 
 // Tokens per work item.
 #define APT_DEFAULT_KV_CHUNK 512
-#define APT_MFMA_HIDDEN_CHUNK 320   // token rows of the MFMA kernel's tile (a multiple of 64)
+#define APT_MFMA_HIDDEN_CHUNK 320       // token rows of the MFMA kernel's tile: 320 ...
+#define APT_MFMA_HIDDEN_CHUNK_SMALL 256 // ... or 256 (default for d_model < APT_MFMA_LARGE_TILE_D_MODEL)
+#define APT_MFMA_LARGE_TILE_D_MODEL 8192
 #define APT_DEFAULT_VALU_HIDDEN_CHUNK 32
 #define APT_MAX_VALU_HIDDEN_CHUNK 64
 #define APT_KV_MAX_PAGES_PER_WAVE 64

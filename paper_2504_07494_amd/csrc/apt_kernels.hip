@@ -351,8 +351,8 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // ---------------------------------------------------------------------------------
 // hidden-kind items, MFMA version (fp16 / bf16, head_dim 128): persistent workgroups
 // ---------------------------------------------------------------------------------
-// Per item: K_h and V_h of a tile of up to kTokTile = 320 tokens, [256 channels] x [320 tokens] with
-// k = d_model, on v_mfma_f32_16x16x32.  The four waves are (mat, th): mat 0 = K_h channels, mat 1 =
+// Per item: K_h and V_h of a tile of up to 320 tokens (TF = 10; described here) or 256 tokens (TF = 8),
+// [256 channels] x [320 tokens] with k = d_model, on v_mfma_f32_16x16x32.  The four waves are (mat, th): mat 0 = K_h channels, mat 1 =
 // V_h channels; th picks the token blocks 2b + th (b = 0..4, 32 tokens each), so a short tile leaves
 // both halves the same number of blocks.  A wave owns a 128 x 160 accumulator tile as 8 x 10 MFMA
 // tiles of 16 x 16: 320 registers, more than the 256 AGPRs, so part of it lives in ordinary VGPRs.
@@ -379,18 +379,20 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // k-tiles of the next item are already on their way into LDS.
 constexpr int kBK = 32;
 constexpr int kRowBytes = kBK * 2;                     // 64 B
-constexpr int kTokFrags = APT_MFMA_HIDDEN_CHUNK / 32;  // X fragments (16 tokens) per wave: 10
-constexpr int kTokTile = 32 * kTokFrags;               // token rows of a tile: 320
-constexpr int kXChunks = kTokTile / 64;                // 1 KB copies of X rows per wave and k-tile: 5
 constexpr int kWTileBytes = 256 * kRowBytes;           // 16 KB
-constexpr int kXTileBytes = kTokTile * kRowBytes;      // 20 KB
 constexpr int kStages = 4;
 constexpr int kXImage = kStages * kWTileBytes;         // LDS offset of the X stages
 constexpr int kMfmaScratch = 5120;                     // epilogue scratch behind the stages
-constexpr int kMfmaLds = kStages * (kWTileBytes + kXTileBytes) + kMfmaScratch;
-constexpr int kStageLoads = 4 + kXChunks;              // copies per wave and k-tile: 4 of W, 5 of X
 constexpr int kFragBytes = 16 * kRowBytes;             // the 16 rows of one MFMA operand fragment
-static_assert(kTokTile % 64 == 0 && kMfmaLds <= 160 * 1024, "tile does not fit");
+// TF = X fragments (16 tokens) per wave: 10 (tile of 320 tokens) or 8 (256 tokens)
+template <int TF> struct MfmaTile {
+    static constexpr int kTokTile = 32 * TF;                   // token rows of a tile
+    static constexpr int kXChunks = kTokTile / 64;             // 1 KB copies of X rows per wave and k-tile
+    static constexpr int kXTileBytes = kTokTile * kRowBytes;   // 20 KB / 16 KB
+    static constexpr int kLds = kStages * (kWTileBytes + kXTileBytes) + kMfmaScratch;
+    static constexpr int kStageLoads = 4 + kXChunks;           // copies per wave and k-tile: 4 of W, then those of X
+    static_assert(kTokTile % 64 == 0 && kLds <= 160 * 1024 && (TF == 8 || TF == 10), "tile does not fit");
+};
 
 // (row >> 2) & 3: free of LDS bank conflicts for 16-byte operand reads of 16 consecutive 64-byte rows
 __host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
@@ -445,9 +447,11 @@ __device__ constexpr int x_frag_off(int f) { return (64 * (f >> 1) + 16 * (f & 1
 // token row (within the tile) of the first token of X fragment f of the wave with token half th
 __device__ inline int x_frag_row(int th, int f) { return th * 32 + 64 * (f >> 1) + 16 * (f & 1); }
 
-template <int DT>
+template <int DT, int TF>
 __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) {
     constexpr int HD = 128;
+    constexpr int kTokFrags = TF, kTokTile = MfmaTile<TF>::kTokTile, kXChunks = MfmaTile<TF>::kXChunks;
+    constexpr int kXTileBytes = MfmaTile<TF>::kXTileBytes, kStageLoads = MfmaTile<TF>::kStageLoads;
     extern __shared__ __align__(16) char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -544,7 +548,8 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     // fragments (NI = 8), B = X fragments (NJ = 2 per valid token block); MAT 1 (V wave): A = X, B = W.  The 64
     // tiles of the first 8 X fragments live in AGPRs (acc_a), the 16 tiles of X fragments 8 and 9 (the fifth
     // token block of the wave) in VGPRs (acc_v).
-    f32x4_t acc_a[64], acc_v[8 * (kTokFrags - 8)];
+    constexpr int kAccV = kTokFrags > 8 ? 8 * (kTokFrags - 8) : 1;     // tiles accumulated in VGPRs (none for TF = 8)
+    f32x4_t acc_a[64], acc_v[kAccV];
     // fr[set][..]: the NI A-side fragments, then the NJ B-side fragments of one k-tile.
     uint4 fr[2][8 + kTokFrags];
     // X fragment and W fragment of tile (I, J)
@@ -648,10 +653,12 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         for (int i = 0; i < 64; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc_a[i][e] = 0.f;
+        if constexpr (kTokFrags > 8) {
 #pragma unroll
-        for (int i = 0; i < 8 * (kTokFrags - 8); ++i)
+            for (int i = 0; i < kAccV; ++i)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc_v[i][e] = 0.f;
+                for (int e = 0; e < 4; ++e) acc_v[i][e] = 0.f;
+        }
 
         APT_OPERAND_ADDRESSES()
         // everything issued so far has to land here: the loads the compiler keeps track of (or the
@@ -664,19 +671,26 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         __syncthreads();
         // a short tile multiplies only the token blocks that hold valid tokens (at least one, so
         // that every wave runs the same barriers)
-        static_assert(kTokFrags == 10, "the dispatch below lists the block counts of a 320-token tile");
-        if (mat == 0) {
-            if (nb == 5) APT_K_LOOP(0, 8, 10)
-            else if (nb == 4) APT_K_LOOP(0, 8, 8)
-            else if (nb == 3) APT_K_LOOP(0, 8, 6)
-            else if (nb == 2) APT_K_LOOP(0, 8, 4)
-            else APT_K_LOOP(0, 8, 2)
-        } else {
-            if (nb == 5) APT_K_LOOP(1, 10, 8)
-            else if (nb == 4) APT_K_LOOP(1, 8, 8)
-            else if (nb == 3) APT_K_LOOP(1, 6, 8)
-            else if (nb == 2) APT_K_LOOP(1, 4, 8)
-            else APT_K_LOOP(1, 2, 8)
+        bool full = false;
+        if constexpr (kTokFrags == 10) {
+            if (nb == 5) {
+                full = true;
+                if (mat == 0) APT_K_LOOP(0, 8, 10)
+                else APT_K_LOOP(1, 10, 8)
+            }
+        }
+        if (!full) {
+            if (mat == 0) {
+                if (nb == 4) APT_K_LOOP(0, 8, 8)
+                else if (nb == 3) APT_K_LOOP(0, 8, 6)
+                else if (nb == 2) APT_K_LOOP(0, 8, 4)
+                else APT_K_LOOP(0, 8, 2)
+            } else {
+                if (nb == 4) APT_K_LOOP(1, 8, 8)
+                else if (nb == 3) APT_K_LOOP(1, 6, 8)
+                else if (nb == 2) APT_K_LOOP(1, 4, 8)
+                else APT_K_LOOP(1, 2, 8)
+            }
         }
 
         // stages 0..2 are free now (every wave has passed the last barrier of the k loop; stage 3
@@ -1042,7 +1056,12 @@ int launch_items(const ItemParams& p, size_t lds_bytes, hipStream_t st) {
 // persistent launch: one workgroup per compute unit, a multiple of 8
 template <int DT>
 int launch_mfma(const ItemParams& p, int n_wg, hipStream_t st) {
-    hipLaunchKernelGGL(apt_items_mfma_kernel<DT>, dim3(n_wg), dim3(kThreads), kMfmaLds, st, p);
+    if (p.hidden_chunk == MfmaTile<10>::kTokTile)
+        hipLaunchKernelGGL((apt_items_mfma_kernel<DT, 10>), dim3(n_wg), dim3(kThreads), MfmaTile<10>::kLds, st, p);
+    else if (p.hidden_chunk == MfmaTile<8>::kTokTile)
+        hipLaunchKernelGGL((apt_items_mfma_kernel<DT, 8>), dim3(n_wg), dim3(kThreads), MfmaTile<8>::kLds, st, p);
+    else
+        return APT_ESHAPE;
     return hipGetLastError() == hipSuccess ? APT_OK : APT_EHIP;
 }
 
@@ -1096,7 +1115,8 @@ int device_setup(const DeviceState** out) {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return APT_EHIP;
         ds.n_wg = cus >= 8 ? (cus / 8) * 8 : 8;
         // every kernel that can be launched with more than 64 KB of dynamic LDS
-        const bool ok = raise_lds_limit(apt_items_mfma_kernel<1>) && raise_lds_limit(apt_items_mfma_kernel<2>) &&
+        const bool ok = raise_lds_limit(apt_items_mfma_kernel<1, 8>) && raise_lds_limit(apt_items_mfma_kernel<2, 8>) &&
+                        raise_lds_limit(apt_items_mfma_kernel<1, 10>) && raise_lds_limit(apt_items_mfma_kernel<2, 10>) &&
                         raise_lds_limit(apt_items_kernel<0, 64, 1>) && raise_lds_limit(apt_items_kernel<0, 128, 1>) &&
                         raise_lds_limit(apt_items_kernel<1, 64, 1>) && raise_lds_limit(apt_items_kernel<1, 128, 1>) &&
                         raise_lds_limit(apt_items_kernel<2, 64, 1>) && raise_lds_limit(apt_items_kernel<2, 128, 1>) &&

@@ -42,8 +42,10 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
     if (s.hidden_impl == APT_HIDDEN_AUTO) s.hidden_impl = mfma_ok ? APT_HIDDEN_MFMA : APT_HIDDEN_VALU;
     if (s.hidden_impl == APT_HIDDEN_MFMA) {
         if (!mfma_ok) return APT_ESHAPE;
-        if (s.hidden_chunk == 0) s.hidden_chunk = APT_MFMA_HIDDEN_CHUNK;
-        if (s.hidden_chunk != APT_MFMA_HIDDEN_CHUNK) return APT_ESHAPE;
+        // the larger tile moves fewer bytes per flop but costs more per item: it pays when an item's k loop is long
+        if (s.hidden_chunk == 0)
+            s.hidden_chunk = s.d_model >= APT_MFMA_LARGE_TILE_D_MODEL ? APT_MFMA_HIDDEN_CHUNK : APT_MFMA_HIDDEN_CHUNK_SMALL;
+        if (s.hidden_chunk != APT_MFMA_HIDDEN_CHUNK && s.hidden_chunk != APT_MFMA_HIDDEN_CHUNK_SMALL) return APT_ESHAPE;
     } else if (s.hidden_impl == APT_HIDDEN_ABSORBED) {
         // heads: groups of 64 rows per operand part on the matrix cores (16-bit inputs), 4 x 10 register tiles otherwise
         const int max_heads = s.dtype == APT_F32 ? APT_ABSORBED_HEAD_GROUPS * APT_ABSORBED_HEADS_PER_THREAD : 128;

@@ -68,6 +68,14 @@ def test_workspace_bound_covers_every_batch(himpl):
     assert e.value.status == ab.APT_ERANGE
 
 
+def test_mfma_tile_default_follows_d_model_and_both_tiles_can_be_asked_for():
+    for kw, want in ((dict(), 256), (dict(d_model=9216, n_heads=72), 320), (dict(hidden_chunk=320), 320),
+                     (dict(d_model=9216, n_heads=72, hidden_chunk=256), 256)):
+        buf, info = _plan(_shape(**kw), [700, 30], [1, 1])
+        assert info.hidden_impl == ab.APT_HIDDEN_MFMA and info.hidden_chunk == want
+        assert info.n_partials == sum(-(-n // want) for n in (700, 30))
+
+
 def _plan(shape, lens, kinds):
     lens = np.asarray(lens, dtype=np.int32)
     kinds = np.asarray(kinds, dtype=np.uint8)
@@ -92,7 +100,7 @@ def test_plan_is_bit_exact_against_the_rule(seed, B, lo, hi, ratio):
     assert info.n_partials == want["n_partials"]
     assert info.total_tokens == int(lens.sum()) and info.hidden_tokens == int(lens[kinds == 1].sum())
     assert info.workspace_bytes == want["n_partials"] * 40 * (128 + 2) * 4
-    assert info.hidden_impl == ab.APT_HIDDEN_MFMA and info.hidden_chunk == 320
+    assert info.hidden_impl == ab.APT_HIDDEN_MFMA and info.hidden_chunk == 256
     # deterministic bytes
     buf2, _ = _plan(shape, lens, kinds)
     assert np.array_equal(buf[:info.plan_bytes // 4], buf2[:info.plan_bytes // 4])
@@ -162,7 +170,7 @@ def test_plan_rejects_bad_arguments():
     (dict(n_heads=39), ab.APT_ESHAPE),                 # H * hd != d
     (dict(head_dim=96, n_heads=40, d_model=3840), ab.APT_ESHAPE),
     (dict(block_size=12), ab.APT_ESHAPE),
-    (dict(hidden_chunk=128), ab.APT_ESHAPE),           # the MFMA tile is 320 tokens
+    (dict(hidden_chunk=128), ab.APT_ESHAPE),           # the MFMA tile is 256 or 320 tokens
     (dict(kv_chunk=100), ab.APT_ESHAPE),               # not a multiple of the block size
     (dict(dtype="f32", hidden_impl=ab.APT_HIDDEN_MFMA), ab.APT_ESHAPE),
     (dict(dtype="f16", out_dtype="bf16"), ab.APT_EDTYPE),

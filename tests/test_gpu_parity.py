@@ -59,16 +59,19 @@ MID = dict(d_model=512, n_heads=4, head_dim=128, block_size=16, batch=7, len_lo=
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-def test_mid_mfma_several_tiles_and_ragged_tails(oracle, dtype):
-    print(f"[case] mid mfma {dtype}", flush=True)
-    cfg = wl.small_config(name="mid", dtype=dtype, **MID)
-    lens = np.array([900, 257, 1, 512, 513, 256, 33], dtype=np.int32)
-    kinds = np.array([HID, HID, HID, KV, KV, HID, KV], dtype=np.uint8)
+@pytest.mark.parametrize("tile", [256, 320])
+def test_mid_mfma_several_tiles_and_ragged_tails(oracle, dtype, tile):
+    """Both token tiles of the MFMA kernel (256: all accumulators in AGPRs; 320: the fifth token block of a wave
+    accumulated in VGPRs), with lengths around every tile and block boundary."""
+    print(f"[case] mid mfma {dtype} tile {tile}", flush=True)
+    cfg = wl.small_config(name="mid", dtype=dtype, **dict(MID, batch=12))
+    lens = np.array([900, 257, 1, 512, 513, 256, 33, 319, 320, 321, 640, 289], dtype=np.int32)
+    kinds = np.array([HID, HID, HID, KV, KV, HID, KV, HID, HID, HID, HID, HID], dtype=np.uint8)
     batch = wl.make_batch(cfg, lens, kinds)
     layer = wl.make_layer(batch)
-    rn, got = _run(batch, layer)
-    assert rn.info.hidden_impl == ab.APT_HIDDEN_MFMA
-    _check(got, _full(oracle, batch, layer), f"mid-mfma-{dtype}", 2e-4, 2e-3)
+    rn, got = _run(batch, layer, hidden_chunk=tile)
+    assert rn.info.hidden_impl == ab.APT_HIDDEN_MFMA and rn.info.hidden_chunk == tile
+    _check(got, _full(oracle, batch, layer), f"mid-mfma-{dtype}-{tile}", 2e-4, 2e-3)
 
 
 @pytest.mark.parametrize("dtype,hd,H,bs", [("f32", 128, 2, 16), ("f16", 64, 4, 16), ("bf16", 64, 4, 8),

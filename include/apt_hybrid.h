@@ -216,7 +216,7 @@ int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens_host, const ui
  * bytes = 2 * d_model^2 elements.  Layout of `packed`, in 16-byte units of 8 elements:
  *   [head][k-tile of 32 inputs][row 0..255][unit 0..3], row < 128: W_K output channel
  *   head*128+row, row >= 128: W_V output channel head*128+row-128; the unit holding
- *   inputs k-tile*32 + 8*c .. +7 sits at position c ^ ((row >> 2) & 3).
+ *   inputs k-tile*32 + 8*c .. +7 sits at position c ^ ((row >> 1) & 3).
  */
 int apt_packed_weight_bytes(const apt_shape* s, size_t* bytes);
 int apt_pack_weights(const apt_shape* s, const void* W_K, const void* W_V, void* packed, void* stream);

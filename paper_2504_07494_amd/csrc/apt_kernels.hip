@@ -369,7 +369,7 @@ __device__ __forceinline__ void hidden_item_valu(const ItemParams& p, int r, int
 // k runs in tiles of 32 (one MFMA k-step) through four LDS stages, each 16 KB of packed weights
 // (already in LDS order in memory) and 20 KB of X rows, filled by global->LDS copies that bypass
 // registers; up to four k-tiles are in flight or waiting while one is multiplied.  Rows are 64 B;
-// the 16-byte unit c of a row sits at c ^ swz(row), which keeps the row-wise copies and the
+// the 16-byte unit c of a row sits at c ^ swz16(row), which keeps the row-wise copies and the
 // column-wise operand reads spread over all banks.  The operands of k-tile kt+1 are read into a
 // second register set while k-tile kt is multiplied.
 //
@@ -394,8 +394,12 @@ template <int TF> struct MfmaTile {
     static_assert(kTokTile % 64 == 0 && kLds <= 160 * 1024 && (TF == 8 || TF == 10), "tile does not fit");
 };
 
-// (row >> 2) & 3: free of LDS bank conflicts for 16-byte operand reads of 16 consecutive 64-byte rows
+// Position swizzles of the 16-byte units of 64-byte LDS rows, measured free of bank conflicts (SQ_LDS_BANK_CONFLICT = 0,
+// 4 cycles per ds_read_b128) for the operand reads of the two MFMA forms: swz for 32x32x16 (a read covers 32 consecutive
+// rows, two units; used by the absorbed-weight kernels), swz16 for 16x16x32 (16 consecutive rows, all four units; with
+// swz it takes 8 cycles).
 __host__ __device__ inline int swz(int row) { return (row >> 2) & 3; }
+__host__ __device__ inline int swz16(int row) { return (row >> 1) & 3; }
 
 template <int DT> __device__ inline f32x16_t mfma32(const uint4& a, const uint4& b, f32x16_t c) {
     if constexpr (DT == 1)
@@ -476,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     static_assert((kTokTile + 3 * 128 + 256 + 8) * 4 <= kMfmaScratch, "epilogue scratch too small");
 
     // This lane's 16 bytes of fragment 0, stage 0, in the W image (the channels of this wave) and in the X image
-    // (the token blocks of this wave): row lane % 16 of the fragment, unit (lane / 16) ^ swz(row); swz does not
+    // (the token blocks of this wave): row lane % 16 of the fragment, unit (lane / 16) ^ swz16(row); swz does not
     // change from fragment to fragment (their first rows are multiples of 16), so every other fragment and stage
     // is a constant offset away.
     // (computed per item, right before its k loop: kept across the epilogue they would sit in scratch)
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
         int ln_ = lane;                                                                                     \
         asm volatile("" : "+v"(ln_));                                                                       \
         const int l16_ = ln_ & 15, qd_ = ln_ >> 4;                                                          \
-        const uint32_t off_ = l16_ * kRowBytes + ((qd_ ^ swz(l16_)) * 16);                                  \
+        const uint32_t off_ = l16_ * kRowBytes + ((qd_ ^ swz16(l16_)) * 16);                                  \
         w_base = lds_base + mat * 128 * kRowBytes + off_;                                                   \
         x_base = lds_base + kXImage + th * 32 * kRowBytes + off_;                                           \
     }
@@ -498,7 +502,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
     int qi = p.plan[APT_PW_QUEUE0 + (g & 7)] + (g >> 3);
 
     // per-lane state of an item: kXChunks X row sources.  An X chunk of 1 KB is 16 rows; wave w
-    // copies chunks w + 4 i: row 16 w + lane/4 + 64 i, LDS unit lane%4 = global unit (lane%4) ^ swz(row)
+    // copies chunks w + 4 i: row 16 w + lane/4 + 64 i, LDS unit lane%4 = global unit (lane%4) ^ swz16(row)
     const int pu = lane & 3, r0 = 16 * w + (lane >> 2);
     int4 it = make_int4(0, 0, 0, 1);
     int32_t ids[kXChunks];
@@ -519,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void apt_items_mfma_kernel(ItemParams p) 
             int tok_ = (ITEM).z + row_;                                                                     \
             tok_ = tok_ < (ITEM).w ? tok_ : (ITEM).w - 1;                                                   \
             XS[i_] = (uint32_t)(((int64_t)BLK[i_] * blk_bytes + ((int64_t)(tok_ & (p.bs - 1)) * d) * 2) >> 4) + \
-                     (pu ^ swz(row_));                                                                      \
+                     (pu ^ swz16(row_));                                                                      \
         }                                                                                                   \
         WS = p.W_packed + (int64_t)(ITEM).y * nkt * kWTileBytes + w * 1024 + lane * 16;                     \
     }
@@ -897,7 +901,7 @@ __global__ __launch_bounds__(kThreads) void apt_pack_kernel(const uint16_t* W_K,
     o.y = v[2] | ((uint32_t)v[3] << 16);
     o.z = v[4] | ((uint32_t)v[5] << 16);
     o.w = v[6] | ((uint32_t)v[7] << 16);
-    packed[((int64_t)h * nkt + kt) * (256 * units) + row * units + (c ^ swz(row))] = o;
+    packed[((int64_t)h * nkt + kt) * (256 * units) + row * units + (c ^ swz16(row))] = o;
 }
 
 // Cache append: one workgroup per request, 16-byte units.  A unit never straddles a head

@@ -97,7 +97,7 @@ def measure(cfg, args, steps, warmup, keep=False):
     batch = wl.make_batch(cfg)
     nl = cfg.n_layers
     himpl = HIMPL[args.hidden_impl]
-    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=himpl)
+    rn = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_chunk=args.hidden_chunk, hidden_impl=himpl)
     layer, dls = None, []
     for li in range(nl):                      # every layer of the step is resident in HBM
         layer = wl.make_layer(batch, layer=li, workers=min(16, os.cpu_count() or 8))
@@ -202,6 +202,8 @@ def main():
     ap.add_argument("--config", default="opt66b")
     ap.add_argument("--hidden-ratio", type=float, default=None)
     ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--hidden-chunk", type=int, default=0,
+                    help="tokens per hidden-kind work item (0 = library default; the MFMA kernel has tiles of 256 and 320)")
     ap.add_argument("--hidden-impl", choices=["auto", "valu", "mfma", "absorbed"], default="auto",
                     help="hidden-kind kernel; 'absorbed' is the re-associated form without K/V projection (its "
                          "roofline entry is priced on its own work, never against the MFMA target)")

@@ -86,7 +86,8 @@ typedef struct apt_shape {
     int32_t dtype;              /* APT_F32 / APT_F16 / APT_BF16: q, pools, W, b           */
     int32_t out_dtype;          /* APT_F32 or the same as dtype                           */
     int32_t max_blocks_per_req; /* row length of block_tables                             */
-    int32_t hidden_chunk;       /* tokens per hidden-kind work item; 0 = library default  */
+    int32_t hidden_chunk;       /* tokens per hidden-kind work item; 0 = library default
+                                   (MFMA kernel: 256 or 320, default 320 for d_model >= 8192)  */
     int32_t kv_chunk;           /* tokens per KV-kind work item; 0 = library default      */
     int32_t hidden_impl;        /* APT_HIDDEN_AUTO: MFMA kernel for 16-bit dtypes with
                                    head_dim 128, plain-ALU kernel otherwise.
@@ -204,7 +205,9 @@ int apt_plan_upload(const void* plan_host, void* plan_dev, void* stream);
  * unified pool; K and V lists for the KV kind, one list for the hidden kind).  Every entry of
  * the first ceil(n/block_size) positions of the rows a request uses must lie in
  * [0, n_pool_blocks).  Returns APT_ERANGE on the first violation, APT_EINVAL for a length < 1 or
- * an unknown kind.
+ * an unknown kind.  Also APT_ERANGE when the resolved hidden_impl is APT_HIDDEN_MFMA and the pool
+ * (n_pool_blocks blocks) is larger than 64 GiB: that kernel addresses hidden rows by 32-bit offsets
+ * in 16-byte units from hidden_pages (a larger pool gives wrong results, not a fault).
  */
 int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens_host, const uint8_t* cache_kind_host,
                       const int32_t* block_tables_host, int B, int64_t n_pool_blocks);

@@ -264,6 +264,10 @@ extern "C" int apt_validate_host(const apt_shape* s, const int32_t* ctx_lens, co
     if (rc) return rc;
     if (!ctx_lens || !cache_kind || !block_tables || B < 1 || n_pool_blocks < 1) return APT_EINVAL;
     const int mb = rs.s.max_blocks_per_req, bs = rs.s.block_size;
+    // the MFMA kernel addresses hidden rows by 32-bit offsets in 16-byte units
+    if (rs.s.hidden_impl == APT_HIDDEN_MFMA &&
+        (uint64_t)n_pool_blocks * (uint64_t)bs * (uint64_t)rs.s.d_model * (uint64_t)rs.elem_bytes > ((uint64_t)1 << 36))
+        return APT_ERANGE;
     for (int r = 0; r < B; ++r) {
         const int n = ctx_lens[r];
         if (n < 1) return APT_EINVAL;

@@ -68,6 +68,17 @@ def test_workspace_bound_covers_every_batch(himpl):
     assert e.value.status == ab.APT_ERANGE
 
 
+def test_validate_host_rejects_a_hidden_pool_beyond_the_mfma_kernels_offset_range():
+    shape = _shape()                                   # block = 16 * 5120 * 2 B = 160 KiB; 64 GiB = 419430.4 blocks
+    lens, kinds = np.array([20], dtype=np.int32), np.array([1], dtype=np.uint8)
+    bt = np.zeros((1, 2, 128), dtype=np.int32)
+    ab.apt_validate_host(shape, lens, kinds, bt, 419430)
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_validate_host(shape, lens, kinds, bt, 419431)
+    assert e.value.status == ab.APT_ERANGE
+    ab.apt_validate_host(_shape(hidden_impl=ab.APT_HIDDEN_ABSORBED), lens, kinds, bt, 419431)
+
+
 def test_mfma_tile_default_follows_d_model_and_both_tiles_can_be_asked_for():
     for kw, want in ((dict(), 256), (dict(d_model=9216, n_heads=72), 320), (dict(hidden_chunk=320), 320),
                      (dict(d_model=9216, n_heads=72, hidden_chunk=256), 256)):

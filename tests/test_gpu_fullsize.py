@@ -124,6 +124,30 @@ def test_opt66b_layer_ratio_sweep(oracle, ratio):
     _run_and_check(oracle, wl.with_ratio(wl.CONFIGS["opt66b"], ratio), n_random=10)
 
 
+@pytest.mark.timeout(300)
+def test_opt66b_every_output_agrees_between_the_three_hidden_paths(oracle):
+    """A property at full size that covers all 256 x 72 (request, head) outputs: the projection kernel with the 320-token
+    tile, the same with the 256-token tile and the absorbed-weight path (another association of Eq. 1-3, other kernels,
+    other plan) agree element by element far inside the parity tolerance; the first of them is the run whose sampled
+    outputs are compared with the oracle here (every request on one head)."""
+    from paper_2504_07494_amd import binding as ab
+    from paper_2504_07494_amd.harness import DecodeRunner
+    cfg = wl.with_ratio(wl.CONFIGS["opt66b"], 0.5)
+    batch, ref = _run_and_check(oracle, cfg, n_random=10)
+    layer = wl.make_layer(batch, workers=16)
+    scale = np.maximum(np.abs(ref), 1e-2)
+    for name, kw in (("tile 256", dict(hidden_chunk=256)), ("absorbed", dict(hidden_impl=ab.APT_HIDDEN_ABSORBED))):
+        print(f"[case] full size {cfg.name} ratio=0.5 {name} against the default path, all outputs", flush=True)
+        rn = DecodeRunner(batch, **kw)
+        rn.run(rn.upload(layer))
+        got = rn.out_f64()
+        a = float(np.abs(got - ref).max())
+        r = float((np.abs(got - ref) / scale).max())
+        print(f"[agree] {name}: max_abs={a:.3e} max_rel={r:.3e} over {got.size} outputs", flush=True)
+        assert np.all(np.isfinite(got)) and a <= 1e-4 and r <= 2e-3
+        del rn
+
+
 @pytest.mark.timeout(900)
 def test_full_decode_step_forty_layers_bf16(oracle):
     """The 40-layer OPT-13B-shaped step: every layer's pool, weights and queries resident in

@@ -212,6 +212,9 @@ def main():
                     help="skip the short extra measurement of the absorbed-weight hidden path (single-layer runs "
                          "of the default hidden path add it under 'next_rows'; it never enters 'value')")
     ap.add_argument("--pairs-per-thread", type=int, default=48)
+    ap.add_argument("--model-layers", type=int, default=64,
+                    help="decoder layers of the model the layer shape belongs to (OPT-66B: 64); only scales the fitted "
+                         "slope into the per-request rho that the scheduling example under 'next_rows' uses")
     ap.add_argument("--sweep", dest="sweep", action="store_true", default=None,
                     help="time hidden-cache ratios 0/25/50/75/100 %% of the config (adds 'sweep' and 'rho_fit'); "
                          "on by default for the default config when no --hidden-ratio is given")
@@ -329,6 +332,8 @@ def main():
         result["rho_fit"] = {"workload": cfg.name, "rho_us_per_hidden_token": slope * 1e3, "intercept_ms": icpt,
                              "r2": 1.0 - float((resid ** 2).sum() / ((y - y.mean()) ** 2).sum()),
                              "points": len(sweep)}
+        if not args.no_next_rows and slope > 0:
+            result.setdefault("next_rows", {})["schedule_with_fitted_rho"] = schedule_with_rho(batch, slope * 1e-3, args)
     if do_extras:
         others = {}
         for name, st, wu in (("opt13b", args.steps, args.warmup), ("opt30b", args.steps, args.warmup),
@@ -336,6 +341,38 @@ def main():
             others[name] = dict(brief(measure(wl.CONFIGS[name], args, st, wu)), steps=st, warmup=wu)
         result["other_configs"] = others
     print(json.dumps(result))
+
+
+def schedule_with_rho(batch, rho_s_per_hidden_token, args):
+    """The measured slope put to its use (Section 4.2, Eq. 6; Section 5, Definition 1): the requests of the bench
+    batch as the candidates of one scheduling iteration.  m_i = the blocks of the request's KV cache (2 per
+    block_size tokens), so a hidden-cache request of m_i costs rho * m_i with rho = slope * layers * block_size / 2;
+    pending times are seeded exponential draws (mean 1 s: light load, mean 30 s: a long queue), the memory limit
+    holds half of all the KV caches, |W| + |R| = batch."""
+    import numpy as np
+    from paper_2504_07494_amd import binding as ab
+    cfg = batch.cfg
+    mem = (2 * -(-batch.ctx_lens.astype(np.int64) // cfg.block_size)).astype(np.int64)
+    limit = int(mem.sum() // 2)
+    rho = rho_s_per_hidden_token * args.model_layers * cfg.block_size / 2.0
+    rows = []
+    for mean_s in (1.0, 30.0):
+        pending = np.random.default_rng(cfg.seed).exponential(mean_s, size=batch.B)
+        alpha, beta, val = ab.apt_schedule(pending, mem, limit, batch.B, rho)
+        t = time.perf_counter()
+        for _ in range(20):
+            ab.apt_schedule(pending, mem, limit, batch.B, rho)
+        ms = (time.perf_counter() - t) / 20 * 1e3
+        order = np.argsort(-pending, kind="stable")      # longest-waiting first, KV cache only, until the memory is full
+        fits = np.cumsum(mem[order]) <= limit
+        kv_only = int(fits.sum()) if fits.all() else int(np.argmin(fits))
+        rows.append({"mean_pending_s": mean_s, "scheduled": int(alpha.sum()),
+                     "with_hidden_cache": int((alpha & beta).sum()),
+                     "memory_used_blocks": int((mem * alpha * (1.0 - beta / 2.0)).sum()), "objective_s": val,
+                     "kv_only_longest_waiting_first": {"scheduled": kv_only, "objective_s": float(pending[order[:kv_only]].sum())},
+                     "ms_per_call": ms})
+    return {"candidates": int(batch.B), "model_layers": args.model_layers, "rho_s_per_block_unit": rho,
+            "memory_limit_blocks": limit, "cases": rows}
 
 
 def run_sched_probe(args):

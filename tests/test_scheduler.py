@@ -165,3 +165,21 @@ def test_schedule_and_pool_compose_admitted_requests_always_fit_and_can_grow():
         assert admitted_hidden > 0 and admitted_kv > 0          # the simulation exercised both cache kinds
     finally:
         ab.apt_pool_destroy(pool)
+
+
+def test_bench_scheduling_example_is_feasible_and_uses_hidden_caches_only_when_waiting_outweighs_recompute():
+    """bench.py's use of the fitted slope (Section 4.2, Eq. 6 into Definition 1): host only."""
+    import types
+    import bench
+    from paper_2504_07494_amd import workloads as wl
+    batch = wl.make_batch(wl.CONFIGS["opt66b"])
+    out = bench.schedule_with_rho(batch, 0.27e-6, types.SimpleNamespace(model_layers=64))
+    light, queue = out["cases"]
+    for c in (light, queue):
+        assert c["memory_used_blocks"] <= out["memory_limit_blocks"]
+        assert c["objective_s"] >= c["kv_only_longest_waiting_first"]["objective_s"] * 0.5     # the rule's guarantee
+        assert c["scheduled"] >= c["kv_only_longest_waiting_first"]["scheduled"]
+    assert light["with_hidden_cache"] == 0 and queue["with_hidden_cache"] > 0
+    # a free recompute (rho = 0) puts every scheduled request on the hidden cache and fits them all in half the memory
+    free = bench.schedule_with_rho(batch, 0.0, types.SimpleNamespace(model_layers=64))["cases"][0]
+    assert free["scheduled"] == free["with_hidden_cache"] == batch.B

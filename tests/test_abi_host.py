@@ -225,6 +225,34 @@ def test_attention_call_rejects_bad_arguments_before_any_launch():
     assert e.value.status == ab.APT_EWORKSPACE
 
 
+def test_static_workspace_call_rejects_bad_arguments_before_any_launch():
+    # the entry point that allocates nothing validates like the ordinary one, and also refuses what its fixed
+    # workspace cannot hold and the absorbed-weight path (no device is touched by any of these calls)
+    shape = _shape()
+    buf, info = _plan(shape, [300, 17], [0, 1])
+    assert info.workspace_bytes <= ab.APT_STATIC_WORKSPACE_BYTES
+    P = 16
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn_static(shape, buf, None, None, None, None, None, None, None, None, None, None,
+                                         None, None)
+    assert e.value.status == ab.APT_EINVAL
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn_static(_shape(block_size=32), buf, P, P, P, P, None, None, None, None, None, None, P, P)
+    assert e.value.status == ab.APT_ESHAPE
+    absorbed = _shape(hidden_impl=ab.APT_HIDDEN_ABSORBED)
+    abuf, _ = _plan(absorbed, [300, 17], [0, 1])
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn_static(absorbed, abuf, P, P, P, P, P, P, P, None, P, P, P, P)
+    assert e.value.status == ab.APT_ESHAPE
+    big = _shape(d_model=9216, n_heads=72, max_blocks_per_req=128)
+    lens = [2048] * 512
+    bbuf, binfo = _plan(big, lens, [0] * len(lens))
+    assert binfo.workspace_bytes > ab.APT_STATIC_WORKSPACE_BYTES
+    with pytest.raises(ab.AptError) as e:
+        ab.apt_hybrid_decode_attn_static(big, bbuf, P, P, P, P, None, None, None, None, None, None, P, P)
+    assert e.value.status == ab.APT_EWORKSPACE
+
+
 def test_cache_write_calls_reject_bad_arguments_before_any_launch():
     shape = _shape()
     P = 16          # any non-null address: validation fails before a launch could use it

@@ -88,7 +88,10 @@ typedef struct apt_shape {
     int32_t max_blocks_per_req; /* row length of block_tables                             */
     int32_t hidden_chunk;       /* tokens per hidden-kind work item; 0 = library default
                                    (MFMA kernel: 256 or 320, default 320 for d_model >= 8192)  */
-    int32_t kv_chunk;           /* tokens per KV-kind work item; 0 = library default      */
+    int32_t kv_chunk;           /* tokens per KV-kind work item, whole blocks, at most 256
+                                   of them; 0 = chosen by apt_plan for each batch: the
+                                   longest of 2048 / 1024 / 512 that still gives 2048
+                                   KV-kind items (apt_plan_info.kv_chunk reports it)      */
     int32_t hidden_impl;        /* APT_HIDDEN_AUTO: MFMA kernel for 16-bit dtypes with
                                    head_dim 128, plain-ALU kernel otherwise.
                                    APT_HIDDEN_ABSORBED (never chosen by AUTO): the same

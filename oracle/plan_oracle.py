@@ -22,6 +22,10 @@ against it bit for bit:
   request, then head.
 * KV-kind items are ordered by decreasing length of their range, ties by request,
   range, head.
+* when the caller leaves kv_chunk open, it is the longest of 2048, 1024 and 512 tokens
+  that consists of whole blocks, at most 256 of them, and with which the KV-kind
+  requests of the batch still make at least 2048 items (ranges x heads); 512 if neither
+  of the longer ones does (auto_kv_chunk below).
 
 Block arithmetic of the cache map (Section 4.3): token j of a request lives in
 its (j // block_size)-th block at slot j % block_size; a request of n tokens owns
@@ -35,6 +39,17 @@ N_QUEUES = 8
 
 def ceil_div(a, b):
     return -(-a // b)
+
+
+def auto_kv_chunk(ctx_lens, cache_kind, n_heads, block_size):
+    """The range length of KV-kind requests when the caller does not fix it."""
+    kv_lens = [int(n) for n, k in zip(ctx_lens, cache_kind) if int(k) == KIND_KV]
+    for c in (2048, 1024):
+        if c % block_size or c // block_size > 256:
+            continue
+        if sum(ceil_div(n, c) for n in kv_lens) * n_heads >= 2048:
+            return c
+    return 512
 
 
 def plan(ctx_lens, cache_kind, n_heads, hidden_chunk, kv_chunk, hidden_item_per_head=True):

@@ -34,7 +34,9 @@ enum {
 #define APT_PLAN_MAGIC 0x41505431
 
 // Tokens per work item.
-#define APT_DEFAULT_KV_CHUNK 512
+#define APT_DEFAULT_KV_CHUNK 512         // shortest range the planner chooses by itself; it doubles it (to at most
+#define APT_MAX_AUTO_KV_CHUNK 2048       // this) while the batch still yields APT_KV_ITEMS_TARGET KV-kind items:
+#define APT_KV_ITEMS_TARGET 2048         // two per workgroup slot of a 256-CU device at four workgroups per CU
 #define APT_MFMA_HIDDEN_CHUNK 320       // token rows of the MFMA kernel's tile: 320 ...
 #define APT_MFMA_HIDDEN_CHUNK_SMALL 256 // ... or 256 (default for d_model < APT_MFMA_LARGE_TILE_D_MODEL)
 #define APT_MFMA_LARGE_TILE_D_MODEL 8192
@@ -62,7 +64,13 @@ enum {
 struct apt_resolved {
     apt_shape s;        // chunks and hidden_impl filled in
     int elem_bytes;
+    bool kv_auto;       // kv_chunk was 0: s.kv_chunk holds the shortest range, the planner may choose a longer one
 };
+
+// Whether c tokens can be a KV-kind range of this shape (whole blocks, within the item kernel's page loop).
+static inline bool apt_kv_chunk_ok(int c, int block_size) {
+    return c >= block_size && c % block_size == 0 && c / block_size <= 4 * APT_KV_MAX_PAGES_PER_WAVE;
+}
 
 // Validates a shape and fills the defaults.  Returns an apt_status.
 int apt_resolve(const apt_shape* in, apt_resolved* out);

@@ -1260,9 +1260,14 @@ static int decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev
     if (pw[APT_PW_MAGIC] != APT_PLAN_MAGIC) return APT_EINVAL;
     // the plan must have been made for this shape
     if (pw[APT_PW_HEADS] != rs.s.n_heads || pw[APT_PW_HEAD_DIM] != rs.s.head_dim || pw[APT_PW_HCHUNK] != rs.s.hidden_chunk ||
-        pw[APT_PW_KCHUNK] != rs.s.kv_chunk || pw[APT_PW_HIMPL] != rs.s.hidden_impl || pw[APT_PW_D_MODEL] != rs.s.d_model ||
+        pw[APT_PW_HIMPL] != rs.s.hidden_impl || pw[APT_PW_D_MODEL] != rs.s.d_model ||
         pw[APT_PW_BLOCK_SIZE] != rs.s.block_size || pw[APT_PW_MAX_BLOCKS] != rs.s.max_blocks_per_req ||
         pw[APT_PW_DTYPE] != rs.s.dtype)
+        return APT_ESHAPE;
+    // KV-kind range length: the caller's, or the planner's choice for this batch when the caller left it open
+    const int kv_chunk = pw[APT_PW_KCHUNK];
+    if (rs.kv_auto ? (kv_chunk < rs.s.kv_chunk || kv_chunk > APT_MAX_AUTO_KV_CHUNK || !apt_kv_chunk_ok(kv_chunk, rs.s.block_size))
+                   : kv_chunk != rs.s.kv_chunk)
         return APT_ESHAPE;
     const int n_items = pw[APT_PW_NITEMS], n_hidden = pw[APT_PW_NHIDDEN];
     const int B = pw[APT_PW_BATCH];
@@ -1317,7 +1322,7 @@ static int decode_attn(const apt_shape* s, const void* plan_host, void* plan_dev
     p.B = B; p.H = rs.s.n_heads; p.d = rs.s.d_model; p.bs = rs.s.block_size; p.log2_bs = log2_bs;
     p.max_blocks = rs.s.max_blocks_per_req;
     p.n_items = n_items; p.n_hidden_items = n_hidden;
-    p.hidden_chunk = rs.s.hidden_chunk; p.kv_chunk = rs.s.kv_chunk; p.items_off = pw[APT_PW_ITEMS_OFF];
+    p.hidden_chunk = rs.s.hidden_chunk; p.kv_chunk = kv_chunk; p.items_off = pw[APT_PW_ITEMS_OFF];
     p.scale_log2e = rs.s.softmax_scale * 1.4426950408889634f;
     hipStream_t st = (hipStream_t)stream;
 

@@ -58,12 +58,9 @@ int apt_resolve(const apt_shape* in, apt_resolved* out) {
     } else {
         return APT_ESHAPE;
     }
-    if (s.kv_chunk == 0) {
-        s.kv_chunk = APT_DEFAULT_KV_CHUNK;
-        if (s.kv_chunk % s.block_size) return APT_ESHAPE;
-    }
-    if (s.kv_chunk < s.block_size || s.kv_chunk % s.block_size != 0) return APT_ESHAPE;
-    if (s.kv_chunk / s.block_size > 4 * APT_KV_MAX_PAGES_PER_WAVE) return APT_ESHAPE;
+    out->kv_auto = s.kv_chunk == 0;
+    if (out->kv_auto) s.kv_chunk = APT_DEFAULT_KV_CHUNK;
+    if (!apt_kv_chunk_ok(s.kv_chunk, s.block_size)) return APT_ESHAPE;
     out->s = s;
     out->elem_bytes = e;
     return APT_OK;
@@ -116,6 +113,18 @@ extern "C" int apt_plan(const apt_shape* s, const int32_t* ctx_lens, const uint8
     if (!ctx_lens || !cache_kind || !plan_host || B < 1) return APT_EINVAL;
     const int H = rs.s.n_heads;
     const int64_t max_len = (int64_t)rs.s.max_blocks_per_req * rs.s.block_size;
+
+    // KV-kind range length left to the library: a short range costs an item's start-up and wind-down more often
+    // per byte, a long one leaves too few items to fill the device; take the longest that still yields enough items
+    if (rs.kv_auto) {
+        for (int c = APT_MAX_AUTO_KV_CHUNK; c > rs.s.kv_chunk; c /= 2) {
+            if (!apt_kv_chunk_ok(c, rs.s.block_size)) continue;
+            int64_t kv_items = 0;
+            for (int r = 0; r < B; ++r)
+                if (cache_kind[r] == APT_KIND_KV && ctx_lens[r] > 0) kv_items += ceil_div64(ctx_lens[r], c) * H;
+            if (kv_items >= APT_KV_ITEMS_TARGET) { rs.s.kv_chunk = c; break; }
+        }
+    }
 
     // pass 1: validate and count
     const bool absorbed = rs.s.hidden_impl == APT_HIDDEN_ABSORBED;

@@ -105,6 +105,7 @@ def test_plan_is_bit_exact_against_the_rule(seed, B, lo, hi, ratio):
     shape = _shape()
     buf, info = _plan(shape, lens, kinds)
     got = ab.decode_plan(buf)
+    assert info.kv_chunk == po.auto_kv_chunk(lens, kinds, 40, 16)
     want = po.plan(lens, kinds, 40, info.hidden_chunk, info.kv_chunk)
     assert got == want
     assert info.n_items == len(want["items"]) and info.n_hidden_items == want["n_hidden_items"]
@@ -208,6 +209,30 @@ def test_validate_host_range_checks_block_ids():
         ab.apt_validate_host(shape, lens, kinds, bt, 7)
 
 
+def test_kv_range_length_left_open_follows_the_batch():
+    """kv_chunk = 0: the longest of 2048 / 1024 / 512 that still yields 2048 KV-kind items; hand-computed cases."""
+    cases = [
+        # (lens, kinds, heads, block size, chosen)
+        ([2048] * 52, [0] * 52, 40, 16, 2048),               # 52 x 40 = 2080 items of 2048 tokens
+        ([2048] * 51, [0] * 51, 40, 16, 1024),               # 2040 < 2048 at 2048, 4080 at 1024
+        ([2048] * 25, [0] * 25, 40, 16, 512),                # 1000, 2000, then 4000 at 512
+        ([2048] * 26, [0] * 26, 40, 16, 1024),               # 2080 at 1024
+        ([16384], [0], 40, 16, 512),                         # one long request: 8 / 16 / 32 ranges x 40 heads
+        ([2048] * 64, [1] * 64, 40, 16, 512),                # no KV-kind request
+        ([2048] * 52 + [2048] * 100, [0] * 52 + [1] * 100, 40, 16, 2048),   # hidden-kind requests do not count
+        ([2048] * 52, [0] * 52, 40, 4, 1024),                # 2048 tokens would be 512 blocks of 4: not allowed
+        ([100] * 60, [0] * 60, 40, 16, 2048),                # short requests: one range each whatever the length
+    ]
+    for lens, kinds, H, bs, want in cases:
+        mb = -(-max(lens) // bs)
+        shape = _shape(d_model=H * 128, n_heads=H, block_size=bs, max_blocks_per_req=mb)
+        _, info = _plan(shape, lens, kinds)
+        assert info.kv_chunk == want == po.auto_kv_chunk(lens, kinds, H, bs), (lens[:2], len(lens), bs)
+        # a length the caller fixes is taken as it is
+        _, info = _plan(_shape(d_model=H * 128, n_heads=H, block_size=bs, max_blocks_per_req=mb, kv_chunk=512), lens, kinds)
+        assert info.kv_chunk == 512
+
+
 def test_attention_call_rejects_bad_arguments_before_any_launch():
     # null pointers and a foreign plan are caught on the host (no device is touched)
     shape = _shape()
@@ -246,7 +271,7 @@ def test_static_workspace_call_rejects_bad_arguments_before_any_launch():
     assert e.value.status == ab.APT_ESHAPE
     big = _shape(d_model=9216, n_heads=72, max_blocks_per_req=128)
     lens = [2048] * 512
-    bbuf, binfo = _plan(big, lens, [0] * len(lens))
+    bbuf, binfo = _plan(big, lens, [1] * len(lens))
     assert binfo.workspace_bytes > ab.APT_STATIC_WORKSPACE_BYTES
     with pytest.raises(ab.AptError) as e:
         ab.apt_hybrid_decode_attn_static(big, bbuf, P, P, P, P, None, None, None, None, None, None, P, P)

@@ -165,6 +165,29 @@ def test_long_contexts_many_ranges_per_request(oracle, impl):
     _check(got, _full(oracle, batch, layer), f"long-{impl}", 2e-4, 2e-3)
 
 
+@pytest.mark.parametrize("kv_chunk,bs", [(1024, 16), (2048, 16), (2048, 8), (0, 16)])
+def test_long_kv_ranges(oracle, kv_chunk, bs):
+    """KV-kind ranges of 1024 and 2048 tokens (the lengths the planner picks by itself for large batches), with
+    lengths around their boundaries, in a mixed batch and as the only kind (kv_chunk 0: 120 requests x 16 heads make the
+    planner choose 1024 here); element by element against the oracle."""
+    print(f"[case] long KV ranges kv_chunk={kv_chunk} block_size={bs}", flush=True)
+    lens = [2048, 2047, 2049, 1024, 1025, 1023, 4096, 4097, 3000, 1, 700, 2050]
+    kinds = [KV, KV, KV, KV, KV, KV, KV, KV, HID, KV, HID, KV]
+    H = 4
+    if kv_chunk == 0:
+        g = np.random.default_rng(5)
+        lens = [int(v) for v in g.integers(900, 1200, size=120)]
+        kinds = [KV] * len(lens)
+        H = 16
+    cfg = wl.small_config(name="longkv", dtype="f16", d_model=128 * H, n_heads=H, head_dim=128, block_size=bs,
+                          batch=len(lens), len_lo=1, len_hi=max(lens), hidden_ratio=0.5)
+    batch = wl.make_batch(cfg, np.array(lens, dtype=np.int32), np.array(kinds, dtype=np.uint8))
+    layer = wl.make_layer(batch)
+    rn, got = _run(batch, layer, kv_chunk=kv_chunk)
+    assert rn.info.kv_chunk == (kv_chunk or 1024)
+    _check(got, _full(oracle, batch, layer), f"longkv-{kv_chunk}-{bs}")
+
+
 @pytest.mark.parametrize("kinds", ["all_kv", "all_hidden"])
 def test_pure_batches_and_single_request(oracle, kinds):
     print(f"[case] pure {kinds}", flush=True)

@@ -2,6 +2,8 @@
 bench.py times: sampled (request, head) outputs against the CPU oracle (each is an
 independent textbook attention the oracle computes on its own), plus properties that hold
 for every element (finite, bit-reproducible, unchanged when the batch is planned again)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -11,11 +13,18 @@ from tests.helpers import oracle_attn
 pytestmark = pytest.mark.gpu
 
 
+FULL = os.environ.get("APT_PARITY_FULL", "") == "1"    # every (request, head) pair: minutes of oracle time per case
+
+
 def _sample_pairs(batch, n_random, seed, every_request=True):
     """Shortest and longest request, lengths = 0, 1, 15 mod 16 when present, both kinds,
     plus random pairs, plus (every_request) one head of EVERY request, drawn so that the
-    requests spread evenly over the eight head queues (head % 8) of the hidden-kind items."""
+    requests spread evenly over the eight head queues (head % 8) of the hidden-kind items.
+    With APT_PARITY_FULL=1 in the environment: every pair."""
     cfg = batch.cfg
+    if FULL:          # APT_PARITY_PART=i/n: the requests r with r % n == i (to split a long case over several runs)
+        i, n = (int(v) for v in os.environ.get("APT_PARITY_PART", "0/1").split("/"))
+        return [(r, h) for r in range(batch.B) if r % n == i for h in range(cfg.n_heads)]
     g = np.random.default_rng(seed)
     lens, kinds = batch.ctx_lens, batch.cache_kind
     picks = []
@@ -38,6 +47,17 @@ def _sample_pairs(batch, n_random, seed, every_request=True):
     return sorted(set(pairs))
 
 
+def _oracle_pairs(oracle, batch, layer, pairs):
+    """The oracle on the given pairs, in slices with a progress line each when there are many (full mode)."""
+    if len(pairs) <= 2048:
+        return oracle_attn(oracle, batch, layer, pairs=pairs)
+    out = []
+    for i in range(0, len(pairs), 1024):
+        out.append(oracle_attn(oracle, batch, layer, pairs=pairs[i:i + 1024]))
+        print(f"  oracle: {min(i + 1024, len(pairs))} of {len(pairs)} pairs", flush=True)
+    return np.concatenate(out)
+
+
 def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_impl=0, every_request=True):
     from paper_2504_07494_amd.harness import DecodeRunner
     print(f"[case] full size {cfg.name} ratio={cfg.hidden_ratio} hidden_impl={hidden_impl}", flush=True)
@@ -49,8 +69,8 @@ def _run_and_check(oracle, cfg, n_random, max_abs=2e-3, max_rel=1e-2, hidden_imp
     got = rn.out_f64()
     assert np.all(np.isfinite(got))
     pairs = _sample_pairs(batch, n_random, cfg.seed, every_request)
-    assert not every_request or {p[0] for p in pairs} == set(range(batch.B))
-    want = oracle_attn(oracle, batch, layer, pairs=pairs)
+    assert FULL or not every_request or {p[0] for p in pairs} == set(range(batch.B))
+    want = _oracle_pairs(oracle, batch, layer, pairs)
     sel = got[[p[0] for p in pairs], [p[1] for p in pairs]]
     err = np.abs(sel - want)
     big = np.abs(want) >= 1e-2
@@ -117,7 +137,7 @@ def test_opt13b_bf16_all_hidden_absorbed_weight_path(oracle):
     _run_and_check(oracle, cfg, n_random=12, hidden_impl=ab.APT_HIDDEN_ABSORBED)
 
 
-@pytest.mark.timeout(300)
+@pytest.mark.timeout(1500 if FULL else 300)
 @pytest.mark.parametrize("ratio", [0.0, 0.25, 0.5, 0.75, 1.0])
 def test_opt66b_layer_ratio_sweep(oracle, ratio):
     """Every point of the hidden-cache ratio sweep bench.py times; every request is compared on at least one head."""
@@ -182,7 +202,7 @@ def test_full_decode_step_forty_layers_bf16(oracle):
     for li in sorted(checked):
         got = outs[li].float().cpu().numpy().astype(np.float64)
         assert np.all(np.isfinite(got))
-        want = oracle_attn(oracle, batch, kept[li], pairs=pairs)
+        want = _oracle_pairs(oracle, batch, kept[li], pairs)
         sel = got[[p[0] for p in pairs], [p[1] for p in pairs]]
         err = np.abs(sel - want)
         big = np.abs(want) >= 1e-2

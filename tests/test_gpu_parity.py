@@ -74,6 +74,22 @@ def test_mid_mfma_several_tiles_and_ragged_tails(oracle, dtype, tile):
     _check(got, _full(oracle, batch, layer), f"mid-mfma-{dtype}-{tile}", 2e-4, 2e-3)
 
 
+@pytest.mark.parametrize("tile,bs,H", [(256, 8, 4), (320, 32, 3), (320, 4, 9), (256, 32, 1)])
+def test_mfma_hidden_path_with_other_block_sizes_and_head_counts(oracle, tile, bs, H):
+    """The MFMA kernel's gather through cache maps of 4-, 8- and 32-token blocks, with head counts that leave some of the
+    eight head queues empty or uneven."""
+    print(f"[case] mfma tile {tile} block_size {bs} heads {H}", flush=True)
+    cfg = wl.small_config(name="mfmabs", dtype="f16", d_model=128 * H, n_heads=H, head_dim=128, block_size=bs,
+                          batch=9, len_lo=1, len_hi=700, hidden_ratio=0.7)
+    lens = np.array([700, 321, 1, 255, 33, 640, 31, 4, 97], dtype=np.int32)
+    kinds = np.array([HID, HID, HID, KV, HID, HID, KV, HID, HID], dtype=np.uint8)
+    batch = wl.make_batch(cfg, lens, kinds)
+    layer = wl.make_layer(batch)
+    rn, got = _run(batch, layer, hidden_chunk=tile)
+    assert rn.info.hidden_impl == ab.APT_HIDDEN_MFMA and rn.info.hidden_chunk == tile
+    _check(got, _full(oracle, batch, layer), f"mfma-{tile}-bs{bs}-H{H}", 2e-4, 2e-3)
+
+
 @pytest.mark.parametrize("dtype,hd,H,bs", [("f32", 128, 2, 16), ("f16", 64, 4, 16), ("bf16", 64, 4, 8),
                                             ("f32", 64, 4, 4), ("f16", 128, 2, 32), ("f16", 128, 2, 4)])
 def test_valu_hidden_and_kv_layout_variants(oracle, dtype, hd, H, bs):

@@ -175,6 +175,45 @@ def measure(cfg, args, steps, warmup, keep=False):
     return m
 
 
+def absorbed_context(batch, layer, rn, args):
+    """Context only: the same step with hidden-kind requests through the absorbed-weight form (no K/V
+    projection: not the paper's method, so it is never the headline and never priced in projection flops)."""
+    import torch
+    from paper_2504_07494_amd import workloads as wl
+    from paper_2504_07494_amd.harness import DecodeRunner
+    cfg = batch.cfg
+    d, e = cfg.d_model, wl.ELEM_BYTES[cfg.dtype]
+    total_tokens, hidden_tokens, kv_tokens = batch.total_tokens, batch.hidden_tokens, batch.kv_tokens
+    rn2 = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=3)
+    dl2 = rn2.upload(layer)
+    for _ in range(3):
+        rn2.plan()
+        rn2.run(dl2)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        rn2.plan()
+        rn2.run(dl2)
+    torch.cuda.synchronize()
+    ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
+    dev = float((rn2.out.float() - rn.out.float()).abs().max())
+    out = {
+        "ms_per_step": ms2, "cached_tokens_per_s": total_tokens / (ms2 * 1e-3),
+        "max_abs_difference_to_default_path": dev,
+        "hbm_frac_on_own_bytes": (2.0 * d * e * kv_tokens + ABSORBED_X_READS * d * e * hidden_tokens) / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    del rn2, dl2
+    return out
+
+
+def resident_bytes(cfg):
+    """HBM a workload keeps resident: per layer its block pool and both forms of the weights."""
+    from paper_2504_07494_amd import workloads as wl
+    e = wl.ELEM_BYTES[cfg.dtype]
+    batch = wl.make_batch(cfg)                               # lengths, kinds and cache maps only: cheap
+    pool = float(batch.n_pool_blocks) * cfg.block_size * cfg.d_model * e
+    return cfg.n_layers * (pool + 4.0 * cfg.d_model ** 2 * e)
+
+
 def sweep_row(ratio, m):
     r = m["roofline"]
     row = {"hidden_ratio": ratio, "total_tokens": m["config"]["total_tokens"], "hidden_tokens": m["config"]["hidden_tokens"],
@@ -299,26 +338,10 @@ def main():
         result["parity_sample"] = {"pairs": int(n_pairs), "max_abs": float(err.max()),
                                    "max_rel": float((err[big] / np.abs(want[big])).max()) if big.any() else 0.0}
     if nl == 1 and himpl == 0 and hidden_tokens > 0 and not args.no_next_rows:
-        # context only: the same step with hidden-kind requests through the absorbed-weight form (no K/V
-        # projection: not the paper's method, so it is never the headline and never priced in projection flops)
-        rn2 = DecodeRunner(batch, kv_chunk=args.kv_chunk, hidden_impl=3)
-        dl2 = rn2.upload(layer)
-        for _ in range(3):
-            rn2.plan()
-            rn2.run(dl2)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            rn2.plan()
-            rn2.run(dl2)
-        torch.cuda.synchronize()
-        ms2 = (time.perf_counter() - t2) * 1e3 / args.steps
-        dev = float((rn2.out.float() - rn.out.float()).abs().max())
-        result["next_rows"] = {"absorbed_weight_hidden_path": {
-            "ms_per_step": ms2, "cached_tokens_per_s": total_tokens / (ms2 * 1e-3),
-            "max_abs_difference_to_default_path": dev,
-            "hbm_frac_on_own_bytes": (2.0 * d * e * kv_tokens + ABSORBED_X_READS * d * e * hidden_tokens) / (ms2 * 1e-3) / 1e9 / PEAK_HBM_GBS}}
-        del rn2, dl2
+        try:
+            result["next_rows"] = {"absorbed_weight_hidden_path": absorbed_context(batch, layer, rn, args)}
+        except Exception as exc:        # noqa: BLE001  (context beside the headline: never costs the line)
+            result["next_rows"] = {"absorbed_weight_hidden_path": {"error": f"{type(exc).__name__}: {exc}"[:300]}}
     del rn, dls, layer
     torch.cuda.empty_cache()
     if sweep:
@@ -338,7 +361,18 @@ def main():
         others = {}
         for name, st, wu in (("opt13b", args.steps, args.warmup), ("opt30b", args.steps, args.warmup),
                              ("opt13b_step", max(2, args.steps // 5), 1)):
-            others[name] = dict(brief(measure(wl.CONFIGS[name], args, st, wu)), steps=st, warmup=wu)
+            # context beside the headline: a workload that cannot run here (say, not enough free HBM for the
+            # 40 resident layers) is reported as such and never costs the line
+            try:
+                need = resident_bytes(wl.CONFIGS[name])
+                free, _ = torch.cuda.mem_get_info()
+                if need > 0.95 * free:
+                    others[name] = {"skipped": f"needs {need / 2**30:.0f} GiB of HBM, {free / 2**30:.0f} GiB free"}
+                    continue
+                others[name] = dict(brief(measure(wl.CONFIGS[name], args, st, wu)), steps=st, warmup=wu)
+            except Exception as exc:        # noqa: BLE001
+                others[name] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+                torch.cuda.empty_cache()
         result["other_configs"] = others
     print(json.dumps(result))
 
